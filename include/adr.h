@@ -1,0 +1,166 @@
+/*
+ * adr.h -- C ABI of the MI355X (gfx950) paged decode-attention library.
+ *
+ * The library implements the per-layer work of the paper's attention executor
+ * (Sec. 3.1 "Overview": an executor colocated with the prefill engine runs the
+ * decode-phase attention that was offloaded to it; Sec. 3.2.1: per layer it
+ * receives the grouped q,k,v of the offloaded requests, runs the attention
+ * kernel over its own KV cache kept in cache blocks with per-request metadata,
+ * and returns the attention output).  The operation itself is step (2) of a
+ * transformer layer in Sec. 2.1: attention of the decode step's single query
+ * token per head over the request's cached K and V, after the new token's K
+ * and V have been added to the cache.
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers, borrowed for the duration of the
+ *    enqueued work; the library never allocates, frees or retains memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue kernels: no synchronisation, no allocation, no copies
+ *    to the host, grids sized from host scalars only, so a call may be recorded
+ *    into a HIP graph (Sec. 3.2.2 relies on replaying pre-launched kernels).
+ *  - Return value: ADR_OK or an error code.  Every host-checkable violation is
+ *    reported BEFORE anything is launched and leaves all buffers untouched.
+ *  - bf16 = upper 16 bits of IEEE binary32.  fp8 = OCP E4M3 (finite-only
+ *    variant: bias 7, max 448, S.1111.111 = NaN).
+ *  - Supported set: d in {64, 128}; page_size = 16; Hq a multiple of Hkv with
+ *    G = Hq/Hkv <= 16; cache dtype bf16 or fp8-e4m3; output bf16 or fp32.
+ *    q-head h reads kv-head h / G.
+ *  - Alignment: q, k_new, v_new, the caches and `out` must be 16-byte aligned
+ *    and row strides must keep every row 16-byte aligned.
+ */
+#ifndef ADR_H
+#define ADR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ADR_OK = 0,
+    ADR_ERR_NULL = 1,        /* a required pointer is NULL */
+    ADR_ERR_SHAPE = 2,       /* a size is non-positive, inconsistent or misaligned */
+    ADR_ERR_UNSUPPORTED = 3, /* outside the supported set above */
+    ADR_ERR_WORKSPACE = 4,   /* split pass requested but workspace missing / too small */
+    ADR_ERR_LAUNCH = 5       /* the HIP runtime refused a launch */
+} adr_status;
+
+typedef enum { ADR_BF16 = 0, ADR_FP8_E4M3 = 1, ADR_F32 = 2 } adr_dtype;
+
+/* Kernel choice for adr_decode_attention (bits 0..3 of `flags`). */
+enum {
+    ADR_KERNEL_AUTO = 0, /* the library picks per shape */
+    ADR_KERNEL_VALU = 1, /* vector-ALU dot products, any supported shape */
+    ADR_KERNEL_MFMA = 2  /* matrix-core QK^T and PV (d = 128, bf16 cache) */
+};
+
+/* The paged KV cache of ONE layer ("cache blocks", Sec. 3.2.1).  K and V are
+ * separate arrays of identical shape [num_pages][page_size][Hkv][d],
+ * contiguous.  Token t of a request lives in page block_table[b][t/page_size],
+ * slot t % page_size.  For fp8 caches each (page, kv-head) has one fp32 scale,
+ * separately for K and V: value = decode(byte) * scale. */
+typedef struct adr_kv_cache {
+    void *k, *v;
+    float *k_scale, *v_scale; /* [num_pages][Hkv]; NULL unless dtype == ADR_FP8_E4M3 */
+    int num_pages, page_size, Hkv, d;
+    adr_dtype dtype;
+} adr_kv_cache;
+
+/*
+ * adr_kv_append -- store the decode step's new token (Sec. 2.1: the decode
+ * phase computes K and V only for the new token; they join the cache).
+ *
+ *   k_new, v_new  bf16 [B][Hkv][d]; request rows `new_row_stride` ELEMENTS
+ *                 apart (so both may be views into one grouped q|k|v buffer,
+ *                 Sec. 3.2.1 step 2); heads and d contiguous.
+ *   block_table   int32 [B][max_pages_per_req], physical page ids.
+ *   positions     int32 [B]: token index to write = request length before the
+ *                 append; negative = skip this row (a padded batch row).
+ *
+ * bf16 cache: a bit-for-bit copy.  fp8 cache: the token landing in slot 0 of a
+ * page sets that page's scale to 2*amax(|x| over d, floored at 2^-20)/448 per
+ * kv-head; every token is stored as round-to-nearest-even, saturating
+ * E4M3(x * (1/scale)) computed in fp32.
+ * A position outside the row's table, or a page id outside [0,num_pages), makes
+ * the kernel skip that row (nothing written); it is not reported.
+ * Two rows naming the same (page, slot) race.
+ */
+int adr_kv_append(const adr_kv_cache *cache, const void *k_new, const void *v_new,
+                  int64_t new_row_stride, const int32_t *block_table, int max_pages_per_req,
+                  const int32_t *positions, int B, void *stream);
+
+/* Bytes of workspace adr_decode_attention needs for a split pass; 0 when
+ * partition_tokens == 0.  Depends only on host scalars. */
+size_t adr_decode_workspace_bytes(int B, int Hq, int d, int max_seq_len, int partition_tokens);
+
+/*
+ * adr_decode_attention -- for every request b and q-head h:
+ *     out[b][h][:] = sum_t softmax_t(scale * <q[b][h], K_t>) * V_t,
+ * t over the first seq_lens[b] cached tokens of request b, K_t/V_t taken from
+ * kv-head h/G (Sec. 2.1 step (2); the kernel the executor of Sec. 3.1 runs).
+ *
+ *   out        [B][Hq][d], bf16 or fp32 (out_dtype), contiguous.
+ *   lse        optional fp32 [B][Hq]: natural-log log-sum-exp of the scaled scores.
+ *   q          bf16 [B][Hq][d], request rows q_row_stride ELEMENTS apart.
+ *   seq_lens   int32 [B]: tokens attended (the length AFTER the append, so the
+ *              new token attends to itself).  0 = padded row: out row = 0,
+ *              lse = -inf, no cache memory is read.
+ *   max_seq_len  host-side upper bound on seq_lens (sizes the grid; a row whose
+ *              seq_len exceeds it is truncated to it).
+ *   partition_tokens  0: one pass per (request, kv-head).  Otherwise a multiple
+ *              of page_size: the sequence is cut into partitions of that many
+ *              tokens, attended independently, and merged by log-sum-exp; needs
+ *              `workspace` of adr_decode_workspace_bytes(...) bytes (256-byte
+ *              aligned).  Rows with a single partition bypass the merge.
+ *   flags      ADR_KERNEL_* in bits 0..3; other bits must be 0.
+ *
+ * Page ids are clamped into [0,num_pages) before use; table entries past
+ * ceil(seq_len/page_size) are never dereferenced.  Results are bit-identical
+ * from run to run for fixed inputs, partition_tokens and flags, and do not
+ * depend on where pages sit in the pool.
+ */
+int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q,
+                         int64_t q_row_stride, const adr_kv_cache *cache,
+                         const int32_t *block_table, int max_pages_per_req,
+                         const int32_t *seq_lens, int B, int Hq, float scale, int max_seq_len,
+                         int partition_tokens, void *workspace, size_t workspace_bytes,
+                         unsigned flags, void *stream);
+
+/*
+ * adr_lse_merge -- combine attention results computed over disjoint token sets
+ * of the same request (the split pass of adr_decode_attention uses it; the
+ * same pair (o, lse) is what a second device would ship for a sequence-sharded
+ * request):
+ *     lse*  = ln sum_p exp(part_lse[p][h])
+ *     out[b][h][:] = sum_p exp(part_lse[p][h] - lse*) * part_o[p][h][:]
+ *
+ *   part_o       fp32 [total_parts][heads][d], each already normalised by its
+ *                own softmax denominator.
+ *   part_lse     fp32 [total_parts][heads], natural log; -inf = empty partition
+ *                (its part_o is ignored, even if NaN).
+ *   part_offsets int32 [B+1]: request b owns partitions [off[b], off[b+1]).
+ *   out          [B][heads][d] bf16 or fp32; lse_out optional fp32 [B][heads].
+ * A request with no partitions, or only empty ones, gives zeros and -inf.
+ */
+int adr_lse_merge(void *out, adr_dtype out_dtype, float *lse_out, const float *part_o,
+                  const float *part_lse, const int32_t *part_offsets, int B, int heads, int d,
+                  void *stream);
+
+/*
+ * Measurement aids (not part of the attention path): a streaming read of
+ * `bytes` bytes (multiple of 16) that folds everything into 4 bytes per
+ * workgroup written to `sink` (>= 64 KiB), and a plain copy.  They give the
+ * box's attainable HBM rate and calibrate the profiler's byte counters.
+ */
+int adr_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+int adr_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+const char *adr_status_string(int status);
+int adr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADR_H */

@@ -1,0 +1,13 @@
+"""MI355X-native paged decode attention: Python binding of the adr C ABI.
+
+The binding only marshals arguments (torch tensors -> device pointers) into
+libadr.so; every step of the path runs in the library's HIP kernels.  There is
+no CPU fallback: if the library is missing, importing the binding's functions
+raises.
+"""
+from .binding import (  # noqa: F401
+    ADR_BF16, ADR_FP8_E4M3, ADR_F32, KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA,
+    AdrError, KVCache, adr_kv_append, adr_decode_attention, adr_decode_workspace_bytes,
+    adr_lse_merge, adr_probe_stream_read, adr_probe_copy, adr_status_string, adr_version,
+    library_path, load_library,
+)

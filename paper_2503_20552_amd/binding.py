@@ -1,0 +1,233 @@
+"""ctypes binding of include/adr.h.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libadr.so")
+
+ADR_BF16, ADR_FP8_E4M3, ADR_F32 = 0, 1, 2
+KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
+
+EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention",
+           "adr_lse_merge", "adr_probe_stream_read", "adr_probe_copy",
+           "adr_status_string", "adr_version")
+
+
+class AdrError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, adr_status_string(status), status))
+
+
+class _CCache(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
+                ("num_pages", ctypes.c_int), ("page_size", ctypes.c_int),
+                ("Hkv", ctypes.c_int), ("d", ctypes.c_int), ("dtype", ctypes.c_int)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libadr.so; fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            "%s is missing: build it with `python -m paper_2503_20552_amd.build` "
+            "(there is no fallback path)" % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, f32, sz, u32 = (ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float,
+                                  ctypes.c_size_t, ctypes.c_uint)
+    lib.adr_kv_append.restype = i32
+    lib.adr_kv_append.argtypes = [ctypes.POINTER(_CCache), vp, vp, i64, vp, i32, vp, i32, vp]
+    lib.adr_decode_workspace_bytes.restype = sz
+    lib.adr_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    lib.adr_decode_attention.restype = i32
+    lib.adr_decode_attention.argtypes = [vp, i32, vp, vp, i64, ctypes.POINTER(_CCache), vp, i32,
+                                         vp, i32, i32, f32, i32, i32, vp, sz, u32, vp]
+    lib.adr_lse_merge.restype = i32
+    lib.adr_lse_merge.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32, i32, vp]
+    lib.adr_probe_stream_read.restype = i32
+    lib.adr_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.adr_probe_copy.restype = i32
+    lib.adr_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.adr_status_string.restype = ctypes.c_char_p
+    lib.adr_status_string.argtypes = [i32]
+    lib.adr_version.restype = i32
+    lib.adr_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def adr_status_string(status: int) -> str:
+    return load_library().adr_status_string(int(status)).decode()
+
+
+def adr_version() -> int:
+    return int(load_library().adr_version())
+
+
+@dataclass
+class KVCache:
+    """One layer's paged cache: k, v [num_pages, page_size, Hkv, d] (bf16, or uint8 fp8 bytes
+    with fp32 k_scale/v_scale [num_pages, Hkv])."""
+    k: torch.Tensor
+    v: torch.Tensor
+    k_scale: Optional[torch.Tensor] = None
+    v_scale: Optional[torch.Tensor] = None
+
+    def c_struct(self) -> _CCache:
+        num_pages, page_size, Hkv, d = self.k.shape
+        if self.k.dtype == torch.bfloat16:
+            dtype = ADR_BF16
+        elif self.k.dtype == torch.uint8:
+            dtype = ADR_FP8_E4M3
+        else:
+            raise TypeError("cache dtype must be bfloat16 or uint8 (fp8 bytes)")
+        if self.v.shape != self.k.shape or self.v.dtype != self.k.dtype:
+            raise ValueError("K and V caches differ in shape or dtype")
+        if not (self.k.is_contiguous() and self.v.is_contiguous()):
+            raise ValueError("caches must be contiguous")
+        for s in (self.k_scale, self.v_scale):
+            if s is not None and (s.dtype != torch.float32 or not s.is_contiguous()
+                                  or tuple(s.shape) != (num_pages, Hkv)):
+                raise ValueError("scales must be contiguous float32 [num_pages, Hkv]")
+        return _CCache(self.k.data_ptr(), self.v.data_ptr(),
+                       self.k_scale.data_ptr() if self.k_scale is not None else None,
+                       self.v_scale.data_ptr() if self.v_scale is not None else None,
+                       num_pages, page_size, Hkv, d, dtype)
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _rows_view(t: torch.Tensor, name: str):
+    """[B, H, d] bf16 with heads and d contiguous; returns (ptr, row stride in elements)."""
+    if t.dtype != torch.bfloat16 or t.dim() != 3:
+        raise TypeError("%s must be bfloat16 [B, heads, d]" % name)
+    if t.stride(2) != 1 or t.stride(1) != t.shape[2]:
+        raise ValueError("%s: heads and d must be contiguous (only the row stride is free)" % name)
+    return t.data_ptr(), t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1] * t.shape[2])
+
+
+def _i32(t: torch.Tensor, name: str):
+    if t.dtype != torch.int32 or not t.is_contiguous():
+        raise TypeError("%s must be contiguous int32" % name)
+    return t.data_ptr()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise AdrError(status, where)
+
+
+def adr_kv_append(cache: KVCache, k_new: torch.Tensor, v_new: torch.Tensor,
+                  block_table: torch.Tensor, positions: torch.Tensor, stream=None) -> None:
+    lib = load_library()
+    cs = cache.c_struct()
+    kp, kstride = _rows_view(k_new, "k_new")
+    vp, vstride = _rows_view(v_new, "v_new")
+    if kstride != vstride:
+        raise ValueError("k_new and v_new must share one row stride")
+    B = k_new.shape[0]
+    if block_table.dim() != 2 or block_table.shape[0] != B or positions.shape != (B,):
+        raise ValueError("block_table [B,max_pages] / positions [B] mismatch")
+    _check(lib.adr_kv_append(ctypes.byref(cs), kp, vp, kstride, _i32(block_table, "block_table"),
+                             block_table.shape[1], _i32(positions, "positions"), B,
+                             _stream_handle(stream)), "adr_kv_append")
+
+
+def adr_decode_workspace_bytes(B: int, Hq: int, d: int, max_seq_len: int,
+                               partition_tokens: int) -> int:
+    return int(load_library().adr_decode_workspace_bytes(B, Hq, d, max_seq_len, partition_tokens))
+
+
+def adr_decode_attention(out: torch.Tensor, q: torch.Tensor, cache: KVCache,
+                         block_table: torch.Tensor, seq_lens: torch.Tensor, scale: float,
+                         max_seq_len: int, partition_tokens: int = 0,
+                         workspace: Optional[torch.Tensor] = None,
+                         lse: Optional[torch.Tensor] = None, flags: int = KERNEL_AUTO,
+                         stream=None) -> None:
+    lib = load_library()
+    cs = cache.c_struct()
+    qp, qstride = _rows_view(q, "q")
+    B, Hq, d = q.shape
+    if out.dtype == torch.bfloat16:
+        odt = ADR_BF16
+    elif out.dtype == torch.float32:
+        odt = ADR_F32
+    else:
+        raise TypeError("out must be bfloat16 or float32")
+    if tuple(out.shape) != (B, Hq, d) or not out.is_contiguous():
+        raise ValueError("out must be contiguous [B, Hq, d]")
+    if lse is not None and (lse.dtype != torch.float32 or tuple(lse.shape) != (B, Hq)
+                            or not lse.is_contiguous()):
+        raise ValueError("lse must be contiguous float32 [B, Hq]")
+    if block_table.dim() != 2 or block_table.shape[0] != B or seq_lens.shape != (B,):
+        raise ValueError("block_table [B,max_pages] / seq_lens [B] mismatch")
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(lib.adr_decode_attention(
+        out.data_ptr(), odt, lse.data_ptr() if lse is not None else None, qp, qstride,
+        ctypes.byref(cs), _i32(block_table, "block_table"), block_table.shape[1],
+        _i32(seq_lens, "seq_lens"), B, Hq, float(scale), int(max_seq_len), int(partition_tokens),
+        ws_ptr, ws_bytes, int(flags), _stream_handle(stream)), "adr_decode_attention")
+
+
+def adr_lse_merge(out: torch.Tensor, part_o: torch.Tensor, part_lse: torch.Tensor,
+                  part_offsets: torch.Tensor, lse_out: Optional[torch.Tensor] = None,
+                  stream=None) -> None:
+    lib = load_library()
+    B, heads, d = out.shape
+    odt = ADR_BF16 if out.dtype == torch.bfloat16 else ADR_F32
+    if out.dtype not in (torch.bfloat16, torch.float32) or not out.is_contiguous():
+        raise TypeError("out must be contiguous bfloat16 or float32")
+    if part_o.dtype != torch.float32 or part_lse.dtype != torch.float32:
+        raise TypeError("partials must be float32")
+    if not (part_o.is_contiguous() and part_lse.is_contiguous()):
+        raise ValueError("partials must be contiguous")
+    if part_o.dim() != 3 or tuple(part_o.shape[1:]) != (heads, d) \
+            or tuple(part_lse.shape) != (part_o.shape[0], heads):
+        raise ValueError("part_o [P,heads,d] / part_lse [P,heads] mismatch")
+    if tuple(part_offsets.shape) != (B + 1,):
+        raise ValueError("part_offsets must be int32 [B+1]")
+    _check(lib.adr_lse_merge(out.data_ptr(), odt,
+                             lse_out.data_ptr() if lse_out is not None else None,
+                             part_o.data_ptr(), part_lse.data_ptr(),
+                             _i32(part_offsets, "part_offsets"), B, heads, d,
+                             _stream_handle(stream)), "adr_lse_merge")
+
+
+def adr_probe_stream_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    n = src.numel() * src.element_size()
+    if sink.numel() * sink.element_size() < 65536:
+        raise ValueError("sink must hold at least 64 KiB")
+    _check(load_library().adr_probe_stream_read(src.data_ptr(), n - n % 16, sink.data_ptr(),
+                                                _stream_handle(stream)), "adr_probe_stream_read")
+
+
+def adr_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    n = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < n:
+        raise ValueError("dst smaller than src")
+    _check(load_library().adr_probe_copy(dst.data_ptr(), src.data_ptr(), n - n % 16,
+                                         _stream_handle(stream)), "adr_probe_copy")

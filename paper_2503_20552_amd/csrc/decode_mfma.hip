@@ -1,0 +1,210 @@
+// Decode attention with the QK^T and PV contractions on the matrix cores
+// (d = 128, bf16 cache, any group size G <= 16).
+//
+// One workgroup of 4 waves per (request, kv-head, partition); wave w streams
+// pages w, w+4, ... .  A page holds exactly 16 tokens = one MFMA tile edge.
+// Lane l is (r, j) = (l % 16, l / 16).
+//
+// QK^T  S[token][head] = K[16 x 128] * Q^T[128 x 16] as four
+//       v_mfma_f32_16x16x32_bf16.  The A operand (K) comes straight from
+//       global memory: lane (r, j) loads, for step kk, the 16 bytes of token r
+//       at chunk kk*4 + j -- the contraction index may be permuted freely as
+//       long as Q^T (the B operand, head r, loaded once) uses the same order.
+//       Heads r >= G are zero columns.
+//       Result layout: lane (r, j) holds S[token 4j+i][head r], i = 0..3.
+// softmax  per lane over its 4 tokens, running max shared across the four
+//       lane groups j by two wave shuffles; fp32 throughout, base 2.
+// PV    O[head][dcol] += P[16 x 16 tokens] * V[16 tokens x 16 dcols], eight
+//       v_mfma_f32_16x16x16_bf16 per page (one per e = 0..7, dcol = 8r + e).
+//       The S layout above IS the A-operand layout (row = head r, k = token
+//       4j+i), so P never moves between lanes.  P is split into a bf16 head
+//       and a bf16 remainder (two MFMAs) so the weights keep ~16 significant
+//       bits.  V is loaded in its natural layout -- lane (r, j), load u: the 16
+//       bytes of token 4j+u at chunk r, i.e. four complete 256-byte rows per
+//       instruction -- and the B operand (k = token 4j+u, n = r) for column
+//       set e is assembled from those four registers with byte permutes.
+//       Result layout: lane (r, j) holds O[head 4j+i][8r + e].
+#include "adr_device.h"
+
+namespace adr {
+
+constexpr int D = 128;
+
+struct PageRegs {
+    u32x4 k[4]; // A operand pieces, step kk
+    u32x4 v[4]; // natural rows, token 4j+u
+};
+
+__device__ __forceinline__ void load_page(PageRegs &pr, const uint16_t *kc, const uint16_t *vc,
+                                          int page, int Hkv, int kvh, int r, int j)
+{
+    const int64_t tok_stride = (int64_t)Hkv * D;
+    const int64_t base = ((int64_t)page * kPageSize * Hkv + kvh) * D;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        pr.k[kk] = *(const u32x4 *)(kc + base + r * tok_stride + (kk * 4 + j) * 8);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        pr.v[u] = *(const u32x4 *)(vc + base + (4 * j + u) * tok_stride + r * 8);
+}
+
+__global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParams p)
+{
+    const int Hkv = p.Hkv, G = p.G;
+    const int kvh = blockIdx.x % Hkv;
+    const int part = (blockIdx.x / Hkv) % p.max_parts;
+    const int b = blockIdx.x / (Hkv * p.max_parts);
+
+    const int L = max(min(p.seq_lens[b], p.max_seq_len), 0);
+    const int n_parts = parts_of(L, p.partition_tokens);
+    if (part >= n_parts)
+        return;
+    const int t0 = p.partition_tokens > 0 ? part * p.partition_tokens : 0;
+    const int t1 = p.partition_tokens > 0 ? min(L, t0 + p.partition_tokens) : L;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 15;
+    const int j = lane >> 4;
+
+    // B operand of QK^T: head r's query, chunk order matching the K loads
+    u32x4 qb[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        qb[kk] = u32x4{0u, 0u, 0u, 0u};
+        if (r < G)
+            qb[kk] = *(const u32x4 *)(p.q + (int64_t)b * p.q_row_stride +
+                                      (int64_t)(kvh * G + r) * D + (kk * 4 + j) * 8);
+    }
+
+    f32x4 o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m = kNegBig; // running max of head r (same value in all four lane groups)
+    float l = 0.f;     // this lane's share of head r's denominator
+
+    const uint16_t *kc = (const uint16_t *)p.k_cache;
+    const uint16_t *vc = (const uint16_t *)p.v_cache;
+    const int32_t *bt = p.block_table + (int64_t)b * p.max_pages;
+    const int pg_end = (t1 + kPageSize - 1) / kPageSize;
+
+    int pg = t0 / kPageSize + wave;
+    PageRegs cur, nxt;
+    if (pg < pg_end)
+        load_page(cur, kc, vc, clamp_page(bt[pg], p.num_pages), Hkv, kvh, r, j);
+
+    for (; pg < pg_end; pg += kWaves) {
+        const bool more = pg + kWaves < pg_end;
+        if (more)
+            load_page(nxt, kc, vc, clamp_page(bt[pg + kWaves], p.num_pages), Hkv, kvh, r, j);
+
+        // ---- S = K Q^T
+        f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8, cur.k[kk]), __builtin_bit_cast(bf16x8, qb[kk]), s, 0, 0, 0);
+
+        const int tok = pg * kPageSize + 4 * j; // first of this lane's four tokens
+        const bool tail = pg * kPageSize + kPageSize > t1;
+        float sc[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sc[i] = s[i] * p.scale_log2e;
+            if (tail && tok + i >= t1)
+                sc[i] = -INFINITY;
+        }
+        if (tail) { // rows of tokens past the end may hold anything: keep them out of P*V
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (tok + u >= t1)
+                    cur.v[u] = u32x4{0u, 0u, 0u, 0u};
+        }
+
+        // ---- online softmax
+        float bm = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+        bm = fmaxf(bm, __shfl_xor(bm, 16));
+        bm = fmaxf(bm, __shfl_xor(bm, 32));
+        if (__any(bm > m)) {
+            const float mn = fmaxf(m, bm);
+            const float alpha = fast_exp2(m - mn);
+            m = mn;
+            l *= alpha;
+            // O rows of this lane are heads 4j+i; their factors sit in lanes with r = 4j+i
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float a = __shfl(alpha, 4 * j + i);
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    o[e][i] *= a;
+            }
+        }
+        uint32_t ph[4], pl[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float pw = fast_exp2(sc[i] - m);
+            l += pw;
+            ph[i] = __float_as_uint(pw) & 0xffff0000u;                 // bf16 head (truncated)
+            pl[i] = __float_as_uint(pw - __uint_as_float(ph[i]));      // remainder, exact in fp32
+        }
+        u32x2 ah, al; // four bf16 each: element i <-> token 4j+i
+        ah[0] = (ph[0] >> 16) | ph[1];
+        ah[1] = (ph[2] >> 16) | ph[3];
+        al[0] = (pl[0] >> 16) | (pl[1] & 0xffff0000u);
+        al[1] = (pl[2] >> 16) | (pl[3] & 0xffff0000u);
+
+        // ---- O += P V
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+            u32x2 vb;
+            vb[0] = __builtin_amdgcn_perm(cur.v[1][e >> 1], cur.v[0][e >> 1], sel);
+            vb[1] = __builtin_amdgcn_perm(cur.v[3][e >> 1], cur.v[2][e >> 1], sel);
+            o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+                __builtin_bit_cast(s16x4, ah), __builtin_bit_cast(s16x4, vb), o[e], 0, 0, 0);
+            o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+                __builtin_bit_cast(s16x4, al), __builtin_bit_cast(s16x4, vb), o[e], 0, 0, 0);
+        }
+        if (more)
+            cur = nxt;
+    }
+
+    // denominators: sum the four lane groups
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+
+    extern __shared__ float lds[];
+    float *sm = lds;                  // [kWaves][G]
+    float *sl = sm + kWaves * G;      // [kWaves][G]
+    float *so = sl + kWaves * G;      // [kWaves][G][D]
+    if (j == 0 && r < G) {
+        sm[wave * G + r] = m;
+        sl[wave * G + r] = l;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int g = 4 * j + i;
+        if (g < G) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                so[(wave * G + g) * D + 8 * r + e] = o[e][i];
+        }
+    }
+    __syncthreads();
+    combine_waves_and_store<D>(p, sm, sl, so, G, b, kvh, part, n_parts);
+}
+
+hipError_t launch_decode_mfma(const DecodeParams &p, int d, hipStream_t stream)
+{
+    if (d != D)
+        return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((int64_t)p.B * p.Hkv * p.max_parts));
+    const size_t lds = (size_t)kWaves * p.G * (D + 2) * sizeof(float);
+    decode_mfma_kernel<<<grid, kThreads, lds, stream>>>(p);
+    return hipGetLastError();
+}
+
+bool decode_mfma_supports(int d, int G) { return d == D && G >= 1 && G <= 16; }
+
+} // namespace adr

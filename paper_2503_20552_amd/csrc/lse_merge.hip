@@ -1,0 +1,81 @@
+// Log-sum-exp merge of per-partition attention results.
+//
+// One group of d/4 threads per (request, head) row; each thread owns four
+// consecutive output elements (16-byte loads of the fp32 partials).  Two sweeps
+// over the row's partitions: the largest lse, then the weighted sum.
+#include "adr_device.h"
+
+namespace adr {
+
+template <int D>
+__global__ __launch_bounds__(256) void lse_merge_kernel(const MergeParams p)
+{
+    constexpr int TPR = D / 4;        // threads per row
+    constexpr int RPB = 256 / TPR;    // rows per block
+    const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / TPR;
+    const int col = (threadIdx.x % TPR) * 4;
+    if (row >= (int64_t)p.B * p.heads)
+        return;
+    const int b = (int)(row / p.heads), h = (int)(row % p.heads);
+
+    int first, count;
+    if (p.part_offsets) {
+        first = p.part_offsets[b];
+        count = p.part_offsets[b + 1] - first;
+    } else {
+        const int L = max(min(p.seq_lens[b], p.max_seq_len), 0);
+        count = parts_of(L, p.partition_tokens);
+        first = b * p.max_parts;
+        if (count <= 1)
+            return; // the attention kernel already wrote this row's final result
+    }
+
+    float top = -INFINITY;
+    for (int i = 0; i < count; ++i)
+        top = fmaxf(top, p.part_lse[(int64_t)(first + i) * p.heads + h]);
+
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    float total = 0.f;
+    if (top > -INFINITY) {
+        for (int i = 0; i < count; ++i) {
+            const int64_t pr = (int64_t)(first + i) * p.heads + h;
+            const float w = fast_exp2((p.part_lse[pr] - top) * kLog2e);
+            if (w > 0.f) { // an empty partition's payload is never touched
+                const f32x4 x = *(const f32x4 *)(p.part_o + pr * D + col);
+                acc += w * x;
+                total += w;
+            }
+        }
+    }
+    const float inv = total > 0.f ? 1.f / total : 0.f;
+    const int64_t off = row * D + col;
+    if (p.out_f32) {
+        *(f32x4 *)((float *)p.out + off) = acc * inv;
+    } else {
+        u32x2 w;
+        w[0] = f32_to_bf16(acc[0] * inv) | (f32_to_bf16(acc[1] * inv) << 16);
+        w[1] = f32_to_bf16(acc[2] * inv) | (f32_to_bf16(acc[3] * inv) << 16);
+        *(u32x2 *)((uint16_t *)p.out + off) = w;
+    }
+    if (p.lse_out && col == 0)
+        p.lse_out[row] = total > 0.f ? top + fast_log2(total) * kLn2 : -INFINITY;
+}
+
+hipError_t launch_lse_merge(const MergeParams &p, hipStream_t stream)
+{
+    const int64_t rows = (int64_t)p.B * p.heads;
+    if (rows == 0)
+        return hipSuccess;
+    if (p.d == 128) {
+        constexpr int RPB = 256 / 32;
+        lse_merge_kernel<128><<<dim3((unsigned)((rows + RPB - 1) / RPB)), 256, 0, stream>>>(p);
+    } else if (p.d == 64) {
+        constexpr int RPB = 256 / 16;
+        lse_merge_kernel<64><<<dim3((unsigned)((rows + RPB - 1) / RPB)), 256, 0, stream>>>(p);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+} // namespace adr

@@ -1,0 +1,130 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching any device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2503_20552_amd as adr
+from paper_2503_20552_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # non-null, 16-byte aligned, never dereferenced on an error path
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "adr.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adr_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = adr.load_library()
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert adr.adr_version() >= 100
+    assert adr.adr_status_string(0) == "ok"
+    assert "unknown" in adr.adr_status_string(99)
+
+
+def cache(**kw):
+    c = dict(k=FAKE, v=FAKE, k_scale=None, v_scale=None, num_pages=8, page_size=16, Hkv=2, d=128,
+             dtype=adr.ADR_BF16)
+    c.update(kw)
+    return binding._CCache(*[c[f] for f, _ in binding._CCache._fields_])
+
+
+def attention(c, **kw):
+    a = dict(out=FAKE, out_dtype=adr.ADR_BF16, lse=None, q=FAKE, q_row_stride=8 * 128, cache=c,
+             block_table=FAKE, max_pages=4, seq_lens=FAKE, B=2, Hq=8, scale=0.1, max_seq_len=64,
+             partition_tokens=0, workspace=None, workspace_bytes=0, flags=0, stream=None)
+    a.update(kw)
+    lib = adr.load_library()
+    return lib.adr_decode_attention(a["out"], a["out_dtype"], a["lse"], a["q"], a["q_row_stride"],
+                                    ctypes.byref(a["cache"]), a["block_table"], a["max_pages"],
+                                    a["seq_lens"], a["B"], a["Hq"], a["scale"], a["max_seq_len"],
+                                    a["partition_tokens"], a["workspace"], a["workspace_bytes"],
+                                    a["flags"], a["stream"])
+
+
+NULL, SHAPE, UNSUP, WORK = 1, 2, 3, 4
+
+
+@pytest.mark.parametrize("kw,expect", [
+    (dict(out=None), NULL), (dict(q=None), NULL), (dict(block_table=None), NULL),
+    (dict(seq_lens=None), NULL),
+    (dict(Hq=7), SHAPE),                       # not a multiple of Hkv
+    (dict(q_row_stride=8 * 128 - 8), SHAPE),   # rows overlap
+    (dict(q_row_stride=8 * 128 + 4), SHAPE),   # rows lose 16-byte alignment
+    (dict(q=FAKE + 2), SHAPE), (dict(out=FAKE + 8), SHAPE),
+    (dict(max_seq_len=65), SHAPE),             # more tokens than the table can name
+    (dict(partition_tokens=24), SHAPE),        # not a multiple of the page size
+    (dict(partition_tokens=-16), SHAPE),
+    (dict(B=-1), SHAPE),
+    (dict(out_dtype=adr.ADR_FP8_E4M3), UNSUP),
+    (dict(flags=3), UNSUP), (dict(flags=16), UNSUP),
+    (dict(Hq=2 * 32, q_row_stride=64 * 128), UNSUP),   # G = 32
+    (dict(partition_tokens=16), WORK),         # split needs a workspace
+    (dict(partition_tokens=16, workspace=FAKE, workspace_bytes=16), WORK),
+    (dict(partition_tokens=16, workspace=FAKE + 16, workspace_bytes=1 << 30), WORK),  # misaligned
+])
+def test_decode_attention_rejects_bad_arguments(kw, expect):
+    assert attention(cache(), **kw) == expect
+
+
+@pytest.mark.parametrize("kw,expect", [
+    (dict(k=None), NULL), (dict(v=None), NULL), (dict(num_pages=0), SHAPE), (dict(Hkv=0), SHAPE),
+    (dict(page_size=32), UNSUP), (dict(d=96), UNSUP), (dict(dtype=adr.ADR_F32), UNSUP),
+    (dict(dtype=adr.ADR_FP8_E4M3), NULL),      # fp8 without scales
+    (dict(k=FAKE + 4), SHAPE),
+])
+def test_cache_descriptor_is_validated(kw, expect):
+    assert attention(cache(**kw)) == expect
+
+
+def test_mfma_only_for_d128_and_valu_only_for_small_groups():
+    assert attention(cache(d=64), flags=adr.KERNEL_MFMA) == UNSUP
+    assert attention(cache(Hkv=1), Hq=16, flags=adr.KERNEL_VALU, q_row_stride=16 * 128) == UNSUP
+
+
+def test_empty_batch_is_ok_without_launch():
+    assert attention(cache(), B=0) == 0
+
+
+def test_append_rejects_bad_arguments():
+    lib = adr.load_library()
+    c = cache()
+
+    def call(**kw):
+        a = dict(k_new=FAKE, v_new=FAKE, stride=2 * 128, bt=FAKE, max_pages=4, pos=FAKE, B=2)
+        a.update(kw)
+        return lib.adr_kv_append(ctypes.byref(c), a["k_new"], a["v_new"], a["stride"], a["bt"],
+                                 a["max_pages"], a["pos"], a["B"], None)
+    assert call(k_new=None) == NULL and call(pos=None) == NULL and call(bt=None) == NULL
+    assert call(stride=128) == SHAPE and call(stride=2 * 128 + 2) == SHAPE
+    assert call(max_pages=0) == SHAPE and call(B=-3) == SHAPE and call(v_new=FAKE + 2) == SHAPE
+    assert call(B=0) == 0
+
+
+def test_merge_rejects_bad_arguments():
+    lib = adr.load_library()
+
+    def call(**kw):
+        a = dict(out=FAKE, dt=adr.ADR_F32, lse=None, po=FAKE, pl=FAKE, off=FAKE, B=1, heads=4, d=128)
+        a.update(kw)
+        return lib.adr_lse_merge(a["out"], a["dt"], a["lse"], a["po"], a["pl"], a["off"], a["B"],
+                                 a["heads"], a["d"], None)
+    assert call(out=None) == NULL and call(po=None) == NULL and call(off=None) == NULL
+    assert call(heads=0) == SHAPE and call(d=100) == UNSUP and call(dt=adr.ADR_FP8_E4M3) == UNSUP
+    assert call(B=0) == 0
+
+
+def test_workspace_size_formula():
+    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1000, 0) == 0
+    rows = 4 * 2 * 8                             # ceil(1000/512) = 2 partitions
+    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1000, 512) == rows * 128 * 4 + 256
+    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1024, 512) == rows * 128 * 4 + 256
+    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1025, 512) > rows * 128 * 4 + 256

@@ -1,0 +1,212 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle
+on the same seeded bytes.  Integer work (append slots, page gather) bit-exact;
+floating point within |gpu-ref| <= 2e-3 + 1e-2*|ref| (bf16 K/V, fp32
+accumulation), and max-abs <= 2e-3 on the fp32-output runs."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_20552_amd as adr
+import workloads as W
+from gpu_util import ATOL, compare, dev, gpu_attention, oracle_attention, say
+
+pytestmark = pytest.mark.gpu
+
+KERNELS = {"valu": adr.KERNEL_VALU, "mfma": adr.KERNEL_MFMA, "auto": adr.KERNEL_AUTO}
+
+
+def small_case(seed, Hq, Hkv, d, lens, pool_pages=0):
+    wl = W.Workload(99, "case", B=len(lens), Hq=Hq, Hkv=Hkv, d=d, lengths="given",
+                    fixed_pool_pages=pool_pages)
+    return W.make_batch(wl, device="cpu", headroom_tokens=1, seed_offset=seed,
+                        lens_before=np.asarray(lens, dtype=np.int32))
+
+
+# ---- workload 1: append, then attend -------------------------------------------
+
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+def test_tiny_workload_append_then_attend(out_dtype):
+    wl = W.WORKLOADS[1]
+    bt = W.make_batch(wl)
+    say("workload 1 append+attend out=%s" % out_dtype)
+    kc, vc = dev(bt.k_cache), dev(bt.v_cache)
+    cache = adr.KVCache(kc, vc)
+    table, pos = dev(bt.block_table), dev(bt.positions)
+    adr.adr_kv_append(cache, dev(bt.k_new), dev(bt.v_new), table, pos)
+    torch.cuda.synchronize()
+    # the oracle's append on a host copy; the whole pool, poison included, must match bit for bit
+    kh, vh = W.bits(bt.k_cache).copy(), W.bits(bt.v_cache).copy()
+    oracle.kv_append(kh, vh, W.bits(bt.k_new), W.bits(bt.v_new), bt.block_table, bt.positions)
+    assert np.array_equal(W.bits(kc), kh) and np.array_equal(W.bits(vc), vh)
+
+    out, lse = gpu_attention(dev(bt.q), kc, vc, table, dev(bt.seq_lens), wl.scale, out_dtype=out_dtype)
+    ref, ref_lse, _ = oracle.decode_attention(W.bits(bt.q), kh, vh, bt.block_table, bt.seq_lens, wl.scale)
+    max_abs, _ = compare(out, lse, ref, ref_lse, what="workload 1")
+    if out_dtype == torch.float32:
+        assert max_abs <= ATOL
+
+
+def test_append_skips_negative_and_out_of_table_positions():
+    b = small_case(1, 8, 2, 128, [5, 16, 31, 40])
+    kc, vc = dev(b.k_cache), dev(b.v_cache)
+    pos = b.positions.copy()
+    pos[1] = -1
+    pos[3] = b.block_table.shape[1] * 16 + 3        # beyond the row's table: skipped, not a fault
+    say("append with skipped rows")
+    adr.adr_kv_append(adr.KVCache(kc, vc), dev(b.k_new), dev(b.v_new), dev(b.block_table), dev(pos))
+    torch.cuda.synchronize()
+    kh, vh = W.bits(b.k_cache).copy(), W.bits(b.v_cache).copy()
+    pos_ok = pos.copy(); pos_ok[3] = -1
+    oracle.kv_append(kh, vh, W.bits(b.k_new), W.bits(b.v_new), b.block_table, pos_ok)
+    assert np.array_equal(W.bits(kc), kh) and np.array_equal(W.bits(vc), vh)
+
+
+def test_append_from_a_grouped_qkv_buffer():
+    """q, k_new, v_new as views into one packed [B, (Hq+2Hkv)*d] buffer."""
+    b = small_case(2, 8, 2, 128, [3, 47, 200])
+    Hq, Hkv, d = 8, 2, 128
+    packed = torch.cat([b.q.reshape(3, -1), b.k_new.reshape(3, -1), b.v_new.reshape(3, -1)], dim=1)
+    packed = dev(packed)
+    qv = packed[:, :Hq * d].view(3, Hq, d)
+    kv = packed[:, Hq * d:(Hq + Hkv) * d].view(3, Hkv, d)
+    vv = packed[:, (Hq + Hkv) * d:].view(3, Hkv, d)
+    assert not qv.is_contiguous()
+    kc, vc = dev(b.k_cache), dev(b.v_cache)
+    say("grouped qkv views")
+    adr.adr_kv_append(adr.KVCache(kc, vc), kv, vv, dev(b.block_table), dev(b.positions))
+    out_v, lse_v = gpu_attention(qv, kc, vc, dev(b.block_table), dev(b.seq_lens), 0.09)
+    out_c, lse_c = gpu_attention(dev(b.q), kc, vc, dev(b.block_table), dev(b.seq_lens), 0.09)
+    assert torch.equal(out_v, out_c) and torch.equal(lse_v, lse_c)
+    kh, vh = W.bits(b.k_cache).copy(), W.bits(b.v_cache).copy()
+    oracle.kv_append(kh, vh, W.bits(b.k_new), W.bits(b.v_new), b.block_table, b.positions)
+    assert np.array_equal(W.bits(kc), kh) and np.array_equal(W.bits(vc), vh)
+
+
+# ---- shapes, tails, kernels, partitions ----------------------------------------------
+
+LENS = [1, 2, 15, 16, 17, 31, 33, 63, 64, 65, 100, 257, 512, 513, 1000, 1499]
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 8, 128), (8, 2, 128), (8, 1, 128), (32, 8, 128),
+                                      (4, 2, 128), (8, 8, 64), (8, 2, 64), (16, 2, 64)])
+@pytest.mark.parametrize("partition_tokens", [0, 64, 512])
+def test_attention_matches_oracle(kernel, Hq, Hkv, d, partition_tokens):
+    if kernel == "mfma" and d != 128:
+        pytest.skip("the matrix-core kernel covers d = 128")
+    b = small_case(10 + Hq + Hkv, Hq, Hkv, d, [L - 1 for L in LENS] + [0])
+    seq = b.seq_lens.copy()
+    seq[-1] = 0                                    # a padded row
+    say("parity kernel=%s Hq=%d Hkv=%d d=%d part=%d" % (kernel, Hq, Hkv, d, partition_tokens))
+    out, lse = gpu_attention(dev(b.q), dev(b.k_cache), dev(b.v_cache), dev(b.block_table), dev(seq),
+                             b.wl.scale, partition_tokens=partition_tokens, flags=KERNELS[kernel])
+    ref, ref_lse = oracle_attention(b.q, b.k_cache, b.v_cache, b.block_table, seq, b.wl.scale)
+    max_abs, max_rel = compare(out, lse, ref, ref_lse, what="%s %d/%d/%d" % (kernel, Hq, Hkv, d))
+    assert max_abs <= ATOL
+    assert torch.all(out[-1] == 0) and torch.isneginf(lse[-1]).all()
+
+
+@pytest.mark.parametrize("kernel", ["mfma"])
+def test_groups_up_to_sixteen_on_the_matrix_cores(kernel):
+    b = small_case(40, 32, 2, 128, [0, 16, 90, 700])
+    say("G=16 mfma")
+    out, lse = gpu_attention(dev(b.q), dev(b.k_cache), dev(b.v_cache), dev(b.block_table),
+                             dev(b.seq_lens), b.wl.scale, flags=KERNELS[kernel], partition_tokens=256)
+    ref, ref_lse = oracle_attention(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.wl.scale)
+    assert compare(out, lse, ref, ref_lse, what="G=16")[0] <= ATOL
+
+
+def test_bf16_output_is_the_rounded_fp32_output():
+    b = small_case(41, 8, 2, 128, [99, 700, 15])
+    args = (dev(b.q), dev(b.k_cache), dev(b.v_cache), dev(b.block_table), dev(b.seq_lens), b.wl.scale)
+    say("bf16 vs fp32 output")
+    for part in (0, 128):
+        o32, _ = gpu_attention(*args, partition_tokens=part)
+        o16, _ = gpu_attention(*args, partition_tokens=part, out_dtype=torch.bfloat16)
+        assert torch.equal(o32.to(torch.bfloat16), o16)
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_run_to_run_and_page_placement_invariance(kernel):
+    b = small_case(42, 8, 2, 128, [700, 33, 1200, 5])
+    table = dev(b.block_table); seq = dev(b.seq_lens); q = dev(b.q)
+    say("determinism kernel=%s" % kernel)
+    a1, l1 = gpu_attention(q, dev(b.k_cache), dev(b.v_cache), table, seq, b.wl.scale,
+                           partition_tokens=256, flags=KERNELS[kernel])
+    a2, l2 = gpu_attention(q, dev(b.k_cache), dev(b.v_cache), table, seq, b.wl.scale,
+                           partition_tokens=256, flags=KERNELS[kernel])
+    assert torch.equal(a1, a2) and torch.equal(l1, l2)
+    rng = np.random.default_rng(7)
+    perm = rng.permutation(b.num_pages)
+    kc2 = torch.empty_like(b.k_cache); vc2 = torch.empty_like(b.v_cache)
+    kc2[torch.from_numpy(perm)] = b.k_cache; vc2[torch.from_numpy(perm)] = b.v_cache
+    a3, l3 = gpu_attention(q, dev(kc2), dev(vc2), dev(perm[b.block_table].astype(np.int32)), seq,
+                           b.wl.scale, partition_tokens=256, flags=KERNELS[kernel])
+    assert torch.equal(a1, a3) and torch.equal(l1, l3)
+
+
+def test_max_seq_len_bound_truncates_rows():
+    b = small_case(43, 8, 2, 128, [300, 40])
+    say("max_seq_len truncation")
+    out, lse = gpu_attention(dev(b.q), dev(b.k_cache), dev(b.v_cache), dev(b.block_table),
+                             dev(b.seq_lens), b.wl.scale, max_seq_len=128, partition_tokens=64)
+    seq = np.minimum(b.seq_lens, 128).astype(np.int32)
+    ref, ref_lse = oracle_attention(b.q, b.k_cache, b.v_cache, b.block_table, seq, b.wl.scale)
+    compare(out, lse, ref, ref_lse, what="truncated")
+
+
+def test_out_of_range_page_ids_are_clamped_not_dereferenced():
+    b = small_case(44, 8, 2, 128, [40, 40])
+    table = b.block_table.copy()
+    table[0, 1] = b.num_pages + 1000               # clamps to the last page
+    table[1, 0] = -5                               # clamps to page 0
+    say("clamped page ids")
+    out, _ = gpu_attention(dev(b.q), dev(b.k_cache), dev(b.v_cache), dev(table), dev(b.seq_lens), b.wl.scale)
+    clamped = np.clip(table, 0, b.num_pages - 1).astype(np.int32)
+    kc = torch.nan_to_num(b.k_cache.float(), nan=0.5).to(torch.bfloat16)
+    vc = torch.nan_to_num(b.v_cache.float(), nan=0.5).to(torch.bfloat16)
+    out2, _ = gpu_attention(dev(b.q), dev(kc), dev(vc), dev(clamped), dev(b.seq_lens), b.wl.scale)
+    out3, _ = gpu_attention(dev(b.q), dev(kc), dev(vc), dev(table), dev(b.seq_lens), b.wl.scale)
+    assert torch.equal(out2, out3)
+
+
+# ---- the public merge ----------------------------------------------------------------
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_lse_merge_matches_oracle(d):
+    rng = np.random.default_rng(50 + d)
+    counts = [0, 1, 2, 7, 33, 1, 0, 128]
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    P, heads = int(off[-1]), 5
+    po = rng.standard_normal((P, heads, d)).astype(np.float32)
+    pl = (rng.standard_normal((P, heads)) * 6).astype(np.float32)
+    pl[3, 2] = -np.inf; po[3, 2] = np.nan                       # an empty partition with a poisoned payload
+    pl[off[4]:off[5], 0] = -np.inf                              # a head with no mass at all
+    say("lse_merge d=%d" % d)
+    for dt in (torch.float32, torch.bfloat16):
+        out = torch.full((len(counts), heads, d), float("nan"), dtype=dt, device="cuda:0")
+        lse = torch.full((len(counts), heads), float("nan"), dtype=torch.float32, device="cuda:0")
+        adr.adr_lse_merge(out, dev(po), dev(pl), dev(off), lse)
+        torch.cuda.synchronize()
+        ref, ref_lse = oracle.lse_merge(po.astype(np.float64), pl.astype(np.float64), off)
+        o = out.float().cpu().numpy().astype(np.float64)
+        tol = 1e-5 if dt == torch.float32 else 2.0 ** -8
+        assert np.all(np.abs(o - ref) <= tol * (1 + np.abs(ref)))
+        lg = lse.cpu().numpy().astype(np.float64)
+        fin = np.isfinite(ref_lse)
+        assert np.array_equal(np.isneginf(lg), ~fin)
+        assert np.all(np.abs(lg[fin] - ref_lse[fin]) <= 1e-5 * (1 + np.abs(ref_lse[fin])))
+
+
+def test_split_equals_unsplit_within_rounding():
+    b = small_case(51, 32, 8, 128, [4000, 513, 77])
+    args = (dev(b.q), dev(b.k_cache), dev(b.v_cache), dev(b.block_table), dev(b.seq_lens), b.wl.scale)
+    say("split vs unsplit")
+    whole, lw = gpu_attention(*args)
+    for part in (16, 512, 2048):
+        split, ls = gpu_attention(*args, partition_tokens=part)
+        assert (whole - split).abs().max().item() < 2e-5
+        assert (lw - ls).abs().max().item() < 2e-5

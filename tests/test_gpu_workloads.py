@@ -1,0 +1,70 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration the
+benchmark times (same partition size, automatic kernel choice, bf16 output),
+against the fp64 oracle: all rows where the oracle finishes in seconds, sampled
+rows otherwise."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_20552_amd as adr
+import workloads as W
+from gpu_util import ATOL, compare, dev, gpu_attention, oracle_attention, say
+
+pytestmark = pytest.mark.gpu
+
+
+def run_workload(ident, rows=None, flags=adr.KERNEL_AUTO):
+    wl = W.WORKLOADS[ident]
+    b = W.make_batch(wl, device="cuda:0")
+    info = W.describe_lengths(b.seq_lens)
+    say("workload %d %s lengths %s pages %d" % (ident, wl.name, info, b.num_pages))
+    cache = adr.KVCache(b.k_cache, b.v_cache)
+    table, pos, seq = dev(b.block_table), dev(b.positions), dev(b.seq_lens)
+    k0, v0 = b.k_cache.clone(), b.v_cache.clone()
+    adr.adr_kv_append(cache, b.k_new, b.v_new, table, pos)
+    torch.cuda.synchronize()
+    # append: exactly the named slots changed, to exactly the new bits
+    pages = torch.from_numpy(b.block_table[np.arange(wl.B), b.positions // 16].astype(np.int64)).cuda()
+    slots = torch.from_numpy((b.positions % 16).astype(np.int64)).cuda()
+    assert torch.equal(b.k_cache[pages, slots].view(torch.int16), b.k_new.view(torch.int16))
+    assert torch.equal(b.v_cache[pages, slots].view(torch.int16), b.v_new.view(torch.int16))
+    k0[pages, slots] = b.k_new; v0[pages, slots] = b.v_new
+    assert torch.equal(k0.view(torch.int16), b.k_cache.view(torch.int16))
+    assert torch.equal(v0.view(torch.int16), b.v_cache.view(torch.int16))
+    del k0, v0
+
+    max_len = int(b.seq_lens.max())
+    res = {}
+    for dt in (torch.bfloat16, torch.float32):
+        out, lse = gpu_attention(b.q, b.k_cache, b.v_cache, table, seq, wl.scale,
+                                 partition_tokens=wl.partition_tokens, flags=flags, out_dtype=dt,
+                                 max_seq_len=max_len)
+        res[dt] = (out, lse)
+    ref, ref_lse = oracle_attention(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, wl.scale, rows=rows)
+    for dt, (out, lse) in res.items():
+        max_abs, max_rel = compare(out, lse, ref, ref_lse, rows=rows, what="workload %d %s" % (ident, dt))
+        say("workload %d out=%s max_abs %.3e max_rel %.3e" % (ident, dt, max_abs, max_rel))
+        if dt == torch.float32:
+            assert max_abs <= ATOL
+
+
+def test_workload_2_llama2_7b_mha_all_rows():
+    run_workload(2)
+
+
+def test_workload_3_llama3_8b_gqa_one_layer_all_rows():
+    run_workload(3)
+
+
+def test_workload_4_colocation_shape_all_rows():
+    run_workload(4)
+
+
+def test_workload_5_length_skew_sampled_rows():
+    wl = W.WORKLOADS[5]
+    lens = W.draw_lengths(wl.lengths, wl.B, np.random.default_rng(wl.seed))
+    long_rows = np.nonzero(lens >= 32768)[0]
+    short_rows = np.nonzero(lens < 32768)[0]
+    rows = np.concatenate([long_rows[:3], [long_rows[np.argmax(lens[long_rows])]], short_rows[:40]])
+    run_workload(5, rows=np.unique(rows).astype(np.int32))
