@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged decode-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 3] [--kernel auto]
+
+A step is one decode iteration of the attention executor over every resident
+layer: per layer adr_kv_append (the new token) then adr_decode_attention
+(partition pass + log-sum-exp merge).  Sequences grow by one token per step.
+Prints ONE JSON line: whole-job attended-KV bandwidth (algorithmic bytes of K
+and V attended per second, inputs resident in HBM), the roofline of the
+dominant kernel from HIP events on the launch stream, and the fp64 oracle timed
+on the host cores as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import paper_2503_20552_amd as adr  # noqa: E402
+import workloads as W  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of this command (see profiles/), scaled by the same counters'
+# reading on adr_probe_copy.  None until such a run has been recorded.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def build_state(wl: W.Workload, layers: int, total_steps: int):
+    dev = "cuda:0"
+    b = W.make_batch(wl, device=dev, headroom_tokens=total_steps + 1)
+    caches = [adr.KVCache(b.k_cache, b.v_cache)]
+    for i in range(1, layers):
+        used = b.used
+        caches.append(adr.KVCache(
+            W.fill_pool_bf16(b.num_pages, wl.page_size, wl.Hkv, wl.d, used, wl.seed + 100 + 2 * i, dev),
+            W.fill_pool_bf16(b.num_pages, wl.page_size, wl.Hkv, wl.d, used, wl.seed + 101 + 2 * i, dev)))
+    # one grouped q|k|v buffer per step, as the executor receives it
+    width = (wl.Hq + 2 * wl.Hkv) * wl.d
+    qkv = W.randn_bf16((wl.B, width), wl.seed + 7, dev)
+    q = qkv[:, :wl.Hq * wl.d].view(wl.B, wl.Hq, wl.d)
+    k_new = qkv[:, wl.Hq * wl.d:(wl.Hq + wl.Hkv) * wl.d].view(wl.B, wl.Hkv, wl.d)
+    v_new = qkv[:, (wl.Hq + wl.Hkv) * wl.d:].view(wl.B, wl.Hkv, wl.d)
+    steps = np.arange(total_steps, dtype=np.int32)[:, None]
+    positions = torch.as_tensor(b.lens_before[None, :] + steps).to(torch.int32).to(dev).contiguous()
+    seq_lens = (positions + 1).contiguous()
+    table = torch.as_tensor(b.block_table).to(dev)
+    max_len = int(b.lens_before.max()) + total_steps
+    return dict(batch=b, caches=caches, q=q, k_new=k_new, v_new=v_new, positions=positions,
+                seq_lens=seq_lens, table=table, max_len=max_len)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=0, help="resident layer caches (0 = the workload's)")
+    ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--partition", type=int, default=-1, help="partition tokens (-1 = the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported, use --gpus 1" % args.gpus, file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    adr.load_library()  # fails loudly when the HIP library is missing
+
+    wl = W.WORKLOADS[args.workload]
+    layers = args.layers or wl.layers
+    part = wl.partition_tokens if args.partition < 0 else args.partition
+    flags = {"auto": adr.KERNEL_AUTO, "valu": adr.KERNEL_VALU, "mfma": adr.KERNEL_MFMA}[args.kernel]
+    K, Wm = args.steps, args.warmup
+    total_steps = K + Wm
+
+    t0 = time.time()
+    st = build_state(wl, layers, total_steps)
+    b = st["batch"]
+    torch.cuda.synchronize()
+    log("workload %d %s: B=%d Hq=%d Hkv=%d d=%d layers=%d partition=%d pool=%d pages (%.1f GB K+V resident) "
+        "lengths %s; set-up %.1f s" % (wl.ident, wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, layers, part, b.num_pages,
+                                      layers * 2 * b.k_cache.numel() * 2 / 1e9, W.describe_lengths(b.seq_lens),
+                                      time.time() - t0))
+    out = torch.empty((wl.B, wl.Hq, wl.d), dtype=torch.bfloat16, device="cuda:0")
+    ws_bytes = adr.adr_decode_workspace_bytes(wl.B, wl.Hq, wl.d, st["max_len"], part)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda:0")
+    bytes_per_token = 2 * wl.Hkv * wl.d * 2          # K and V, bf16, one layer
+
+    def one_step(s, events=None):
+        pos, seq = st["positions"][s], st["seq_lens"][s]
+        for li, cache in enumerate(st["caches"]):
+            adr.adr_kv_append(cache, st["k_new"], st["v_new"], st["table"], pos)
+            if events is None:
+                adr.adr_decode_attention(out, st["q"], cache, st["table"], seq, wl.scale, st["max_len"],
+                                         part, ws, None, flags)
+            else:   # same kernels, same order, with an event between the two passes
+                e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+                e0.record()
+                adr.adr_decode_attention(out, st["q"], cache, st["table"], seq, wl.scale, st["max_len"],
+                                         part, ws, None, flags | adr.PARTIALS_ONLY)
+                e1.record()
+                adr.adr_decode_merge(out, seq, st["max_len"], part, ws)
+                e2.record()
+                events.append((e0, e1, e2))
+
+    for s in range(Wm):
+        one_step(s)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for s in range(Wm, Wm + K):
+        one_step(s)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+
+    tokens_per_step = [int(b.lens_before.sum()) + wl.B * (s + 1) for s in range(Wm, Wm + K)]
+    attended_tokens = layers * sum(tokens_per_step)          # (token, layer) pairs attended
+    kv_bytes = attended_tokens * bytes_per_token
+    value = kv_bytes / elapsed / 1e9
+
+    # the same K steps again, instrumented: HIP events on the launch stream around each pass
+    events = []
+    for s in range(Wm, Wm + K):
+        one_step(s, events)
+    torch.cuda.synchronize()
+    attn_ms = np.array([e0.elapsed_time(e1) for e0, e1, _ in events])
+    merge_ms = np.array([e1.elapsed_time(e2) for _, e1, e2 in events])
+    bytes_per_launch = kv_bytes / (layers * K)
+    achieved = bytes_per_launch / (attn_ms.mean() * 1e-3) / 1e9
+    kernel_name = "decode_mfma_kernel" if (flags == adr.KERNEL_MFMA or (flags == adr.KERNEL_AUTO and wl.d == 128)) \
+        else "decode_valu_kernel"
+    traffic = MEASURED_TRAFFIC_BYTES.get((wl.ident, kernel_name))
+    roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "avg_kernel_ms": round(float(attn_ms.mean()), 5), "launches": int(len(attn_ms)),
+                "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                "merge_avg_ms": round(float(merge_ms.mean()), 5)}
+    log("partition pass %.4f ms avg (min %.4f, max %.4f), merge %.4f ms avg" % (
+        attn_ms.mean(), attn_ms.min(), attn_ms.max(), merge_ms.mean()))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(wl, st, Wm)
+
+    line = {
+        "metric": "decode_attention_attended_kv_bandwidth",
+        "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(elapsed / K * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d page=16 bf16, %d resident layers, partition %d + LSE merge, "
+                               "lengths %s" % (wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, layers, part, wl.lengths),
+                   "kernel": args.kernel, "layers": layers, "partition_tokens": part},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
+        "attended_tokens_per_s": round(attended_tokens / elapsed, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+def cpu_baseline(wl, st, step):
+    """The fp64 oracle, untuned, on this machine's host cores over a bounded sample:
+    whole layers of the same workload at the first timed step's lengths, as many
+    as give roughly 10-30 s of CPU work."""
+    import oracle
+    b = st["batch"]
+    seq = st["seq_lens"][step].cpu().numpy()
+    pairs_per_layer = int(seq.sum()) * wl.Hq                 # (token, q-head) dot products and V sums
+    n_layers = int(min(len(st["caches"]), max(1, round(1.0e8 / max(pairs_per_layer, 1)))))
+    qh = W.bits(st["q"].contiguous())
+    dt, threads = 0.0, 1
+    for li in range(n_layers):
+        cache = st["caches"][li]
+        kh, vh = W.bits(cache.k), W.bits(cache.v)           # device -> host copy, not timed
+        t0 = time.perf_counter()
+        _, _, threads = oracle.decode_attention(qh, kh, vh, b.block_table, seq, wl.scale)
+        dt += time.perf_counter() - t0
+        del kh, vh
+    tokens = int(seq.sum()) * n_layers
+    gbs = tokens * 2 * wl.Hkv * wl.d * 2 / dt / 1e9
+    log("cpu oracle: %d layer(s), %d attended tokens, %.2f s on %d threads -> %.3f GB/s" % (
+        n_layers, tokens, dt, threads, gbs))
+    return {"value": round(gbs, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "sample": "fp64 oracle over %d of %d layers, all %d requests (%d attended token-layers), %.2f s wall"
+                      % (n_layers, len(st["caches"]), wl.B, tokens, dt),
+            "attended_tokens_per_s": round(tokens / dt, 1)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -53,7 +53,12 @@ typedef enum { ADR_BF16 = 0, ADR_FP8_E4M3 = 1, ADR_F32 = 2 } adr_dtype;
 enum {
     ADR_KERNEL_AUTO = 0, /* the library picks per shape */
     ADR_KERNEL_VALU = 1, /* vector-ALU dot products, any supported shape */
-    ADR_KERNEL_MFMA = 2  /* matrix-core QK^T and PV (d = 128, bf16 cache) */
+    ADR_KERNEL_MFMA = 2, /* matrix-core QK^T and PV (d = 128, bf16 cache) */
+    /* Bit 4: run the partition pass only and leave the merge to a later
+     * adr_decode_merge call on the same workspace (rows with one partition are
+     * still written to `out` directly).  Lets a caller place the two passes on
+     * a stream itself, e.g. to time them separately. */
+    ADR_PARTIALS_ONLY = 16
 };
 
 /* The paged KV cache of ONE layer ("cache blocks", Sec. 3.2.1).  K and V are
@@ -114,7 +119,8 @@ size_t adr_decode_workspace_bytes(int B, int Hq, int d, int max_seq_len, int par
  *              tokens, attended independently, and merged by log-sum-exp; needs
  *              `workspace` of adr_decode_workspace_bytes(...) bytes (256-byte
  *              aligned).  Rows with a single partition bypass the merge.
- *   flags      ADR_KERNEL_* in bits 0..3; other bits must be 0.
+ *   flags      ADR_KERNEL_* in bits 0..3, optionally | ADR_PARTIALS_ONLY; other
+ *              bits must be 0.
  *
  * Page ids are clamped into [0,num_pages) before use; table entries past
  * ceil(seq_len/page_size) are never dereferenced.  Results are bit-identical
@@ -127,6 +133,19 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
                          const int32_t *seq_lens, int B, int Hq, float scale, int max_seq_len,
                          int partition_tokens, void *workspace, size_t workspace_bytes,
                          unsigned flags, void *stream);
+
+/*
+ * adr_decode_merge -- the second pass of a split adr_decode_attention that was
+ * called with ADR_PARTIALS_ONLY: merges the partitions left in `workspace` into
+ * out / lse for every row with more than one partition; other rows are left as
+ * the first pass wrote them.  B, Hq, d, seq_lens, max_seq_len, partition_tokens
+ * and the workspace must be those of the first pass.  A no-op (ADR_OK) when the
+ * first pass did not split (max_seq_len <= partition_tokens or partition_tokens
+ * == 0).
+ */
+int adr_decode_merge(void *out, adr_dtype out_dtype, float *lse, const int32_t *seq_lens, int B,
+                     int Hq, int d, int max_seq_len, int partition_tokens, const void *workspace,
+                     size_t workspace_bytes, void *stream);
 
 /*
  * adr_lse_merge -- combine attention results computed over disjoint token sets

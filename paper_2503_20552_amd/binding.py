@@ -13,9 +13,10 @@ _LIB_PATH = os.path.join(_HERE, "libadr.so")
 
 ADR_BF16, ADR_FP8_E4M3, ADR_F32 = 0, 1, 2
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
+PARTIALS_ONLY = 16
 
 EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention",
-           "adr_lse_merge", "adr_probe_stream_read", "adr_probe_copy",
+           "adr_decode_merge", "adr_lse_merge", "adr_probe_stream_read", "adr_probe_copy",
            "adr_status_string", "adr_version")
 
 
@@ -58,6 +59,8 @@ def load_library():
     lib.adr_decode_attention.restype = i32
     lib.adr_decode_attention.argtypes = [vp, i32, vp, vp, i64, ctypes.POINTER(_CCache), vp, i32,
                                          vp, i32, i32, f32, i32, i32, vp, sz, u32, vp]
+    lib.adr_decode_merge.restype = i32
+    lib.adr_decode_merge.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
     lib.adr_lse_merge.restype = i32
     lib.adr_lse_merge.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32, i32, vp]
     lib.adr_probe_stream_read.restype = i32
@@ -191,6 +194,23 @@ def adr_decode_attention(out: torch.Tensor, q: torch.Tensor, cache: KVCache,
         ctypes.byref(cs), _i32(block_table, "block_table"), block_table.shape[1],
         _i32(seq_lens, "seq_lens"), B, Hq, float(scale), int(max_seq_len), int(partition_tokens),
         ws_ptr, ws_bytes, int(flags), _stream_handle(stream)), "adr_decode_attention")
+
+
+def adr_decode_merge(out: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,
+                     partition_tokens: int, workspace: Optional[torch.Tensor],
+                     lse: Optional[torch.Tensor] = None, stream=None) -> None:
+    lib = load_library()
+    B, Hq, d = out.shape
+    if out.dtype not in (torch.bfloat16, torch.float32) or not out.is_contiguous():
+        raise TypeError("out must be contiguous bfloat16 or float32")
+    odt = ADR_BF16 if out.dtype == torch.bfloat16 else ADR_F32
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(lib.adr_decode_merge(out.data_ptr(), odt, lse.data_ptr() if lse is not None else None,
+                                _i32(seq_lens, "seq_lens"), B, Hq, d, int(max_seq_len),
+                                int(partition_tokens), ws_ptr, ws_bytes, _stream_handle(stream)),
+           "adr_decode_merge")
 
 
 def adr_lse_merge(out: torch.Tensor, part_o: torch.Tensor, part_lse: torch.Tensor,

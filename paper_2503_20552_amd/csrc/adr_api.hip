@@ -129,7 +129,7 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
         return ADR_ERR_UNSUPPORTED;
     if (partition_tokens < 0 || partition_tokens % adr::kPageSize != 0)
         return ADR_ERR_SHAPE;
-    if (flags & ~0xFu)
+    if (flags & ~(0xFu | ADR_PARTIALS_ONLY))
         return ADR_ERR_UNSUPPORTED;
     const int G = Hq / cache->Hkv;
     const int d = cache->d;
@@ -201,7 +201,7 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
                             : adr::launch_decode_valu(p, d, (hipStream_t)stream);
     if (e != hipSuccess)
         return ADR_ERR_LAUNCH;
-    if (split) {
+    if (split && !(flags & ADR_PARTIALS_ONLY)) {
         adr::MergeParams mp;
         mp.out = out;
         mp.lse_out = lse;
@@ -221,6 +221,43 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
             return ADR_ERR_LAUNCH;
     }
     return ADR_OK;
+}
+
+int adr_decode_merge(void *out, adr_dtype out_dtype, float *lse, const int32_t *seq_lens, int B,
+                     int Hq, int d, int max_seq_len, int partition_tokens, const void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    if (!out || !seq_lens)
+        return ADR_ERR_NULL;
+    if (B < 0 || Hq <= 0 || max_seq_len < 0 || partition_tokens < 0 ||
+        partition_tokens % adr::kPageSize != 0 || !aligned16(out))
+        return ADR_ERR_SHAPE;
+    if (d != 64 && d != 128)
+        return ADR_ERR_UNSUPPORTED;
+    if (out_dtype != ADR_BF16 && out_dtype != ADR_F32)
+        return ADR_ERR_UNSUPPORTED;
+    const int64_t max_parts = max_parts_for(max_seq_len, partition_tokens);
+    if (partition_tokens == 0 || max_parts <= 1 || B == 0)
+        return ADR_OK;
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 ||
+        workspace_bytes < adr_decode_workspace_bytes(B, Hq, d, max_seq_len, partition_tokens))
+        return ADR_ERR_WORKSPACE;
+    const size_t rows = (size_t)B * (size_t)max_parts * Hq;
+    adr::MergeParams mp;
+    mp.out = out;
+    mp.lse_out = lse;
+    mp.part_o = (const float *)workspace;
+    mp.part_lse = (const float *)((const char *)workspace + round256(rows * d * sizeof(float)));
+    mp.part_offsets = nullptr;
+    mp.seq_lens = seq_lens;
+    mp.partition_tokens = partition_tokens;
+    mp.max_parts = (int)max_parts;
+    mp.max_seq_len = max_seq_len;
+    mp.B = B;
+    mp.heads = Hq;
+    mp.d = d;
+    mp.out_f32 = out_dtype == ADR_F32;
+    return adr::launch_lse_merge(mp, (hipStream_t)stream) == hipSuccess ? ADR_OK : ADR_ERR_LAUNCH;
 }
 
 int adr_lse_merge(void *out, adr_dtype out_dtype, float *lse_out, const float *part_o,
