@@ -35,17 +35,104 @@ struct PageRegs {
     u32x4 v[4]; // natural rows, token 4j+u
 };
 
-__device__ __forceinline__ void load_page(PageRegs &pr, const uint16_t *kc, const uint16_t *vc,
-                                          int page, int Hkv, int kvh, int r, int j)
+// Buffer descriptor of one cache page: base = the page, range = the page's
+// bytes (reads past it return zero instead of touching memory), raw 32-bit
+// addressing.  Built from wave-uniform values, so it lives in scalar registers
+// and every load is "descriptor + 32-bit lane offset + scalar offset".
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t page_rsrc(const char *cache, int page,
+                                                            uint32_t page_bytes)
 {
-    const int64_t tok_stride = (int64_t)Hkv * D;
-    const int64_t base = ((int64_t)page * kPageSize * Hkv + kvh) * D;
+    return __builtin_amdgcn_make_buffer_rsrc((void *)(cache + (size_t)page * page_bytes), 0,
+                                             (int)page_bytes, 0x00020000);
+}
+
+// Issue the eight 16-byte loads of one page (this lane's share of K and V for
+// one kv-head).
+__device__ __forceinline__ void load_page(PageRegs &pr, __amdgpu_buffer_rsrc_t krsrc,
+                                          __amdgpu_buffer_rsrc_t vrsrc, uint32_t k_lane,
+                                          uint32_t v_lane, uint32_t tok_bytes)
+{
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
-        pr.k[kk] = *(const u32x4 *)(kc + base + r * tok_stride + (kk * 4 + j) * 8);
+        pr.k[kk] = __builtin_amdgcn_raw_buffer_load_b128(krsrc, k_lane, kk * 64, 0);
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-        pr.v[u] = *(const u32x4 *)(vc + base + (4 * j + u) * tok_stride + r * 8);
+        pr.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrsrc, v_lane, u * tok_bytes, 0);
+}
+
+struct WaveState {
+    f32x4 o[8]; // O[head 4j+i][8r+e]
+    float m;    // running max of head r (same value in all four lane groups)
+    float l;    // this lane's share of head r's denominator
+};
+
+// One page: S = K Q^T, online softmax, O += P V.
+__device__ __forceinline__ void attend_page(WaveState &st, PageRegs &pg, const u32x4 (&qb)[4],
+                                            float scale_log2e, int tok, int t1, int j)
+{
+    f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pg.k[kk]),
+                                                    __builtin_bit_cast(bf16x8, qb[kk]), s, 0, 0, 0);
+    // tok = index of the first of this lane's four tokens (4j + i)
+    const bool tail = tok - 4 * j + kPageSize > t1;
+    float sc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        sc[i] = s[i] * scale_log2e;
+        if (tail && tok + i >= t1)
+            sc[i] = -INFINITY;
+    }
+    if (tail) { // rows of tokens past the end may hold anything: keep them out of P*V
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (tok + u >= t1)
+                pg.v[u] = u32x4{0u, 0u, 0u, 0u};
+    }
+
+    float bm = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+    bm = fmaxf(bm, __shfl_xor(bm, 16));
+    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    if (__any(bm > st.m)) {
+        const float mn = fmaxf(st.m, bm);
+        const float alpha = fast_exp2(st.m - mn);
+        st.m = mn;
+        st.l *= alpha;
+        // O rows of this lane are heads 4j+i; their factors sit in lanes with r = 4j+i
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float a = __shfl(alpha, 4 * j + i);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                st.o[e][i] *= a;
+        }
+    }
+    uint32_t ph[4], pl[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float pw = fast_exp2(sc[i] - st.m);
+        st.l += pw;
+        ph[i] = __float_as_uint(pw) & 0xffff0000u;            // bf16 head (truncated)
+        pl[i] = __float_as_uint(pw - __uint_as_float(ph[i])); // remainder, exact in fp32
+    }
+    u32x2 ah, al; // four bf16 each: element i <-> token 4j+i
+    ah[0] = (ph[0] >> 16) | ph[1];
+    ah[1] = (ph[2] >> 16) | ph[3];
+    al[0] = (pl[0] >> 16) | (pl[1] & 0xffff0000u);
+    al[1] = (pl[2] >> 16) | (pl[3] & 0xffff0000u);
+
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        u32x2 vb;
+        vb[0] = __builtin_amdgcn_perm(pg.v[1][e >> 1], pg.v[0][e >> 1], sel);
+        vb[1] = __builtin_amdgcn_perm(pg.v[3][e >> 1], pg.v[2][e >> 1], sel);
+        st.o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+            __builtin_bit_cast(s16x4, ah), __builtin_bit_cast(s16x4, vb), st.o[e], 0, 0, 0);
+        st.o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+            __builtin_bit_cast(s16x4, al), __builtin_bit_cast(s16x4, vb), st.o[e], 0, 0, 0);
+    }
 }
 
 __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParams p)
@@ -77,100 +164,56 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
                                       (int64_t)(kvh * G + r) * D + (kk * 4 + j) * 8);
     }
 
-    f32x4 o[8];
+    WaveState st;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-        o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m = kNegBig; // running max of head r (same value in all four lane groups)
-    float l = 0.f;     // this lane's share of head r's denominator
+        st.o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    st.m = kNegBig;
+    st.l = 0.f;
 
-    const uint16_t *kc = (const uint16_t *)p.k_cache;
-    const uint16_t *vc = (const uint16_t *)p.v_cache;
+    // byte offsets of this lane inside a page: K: token r, chunk j (+ 4 per step); V: token 4j, chunk r
+    const uint32_t tok_bytes = (uint32_t)Hkv * D * 2;
+    const uint32_t k_lane = (uint32_t)kvh * D * 2 + r * tok_bytes + j * 16;
+    const uint32_t v_lane = (uint32_t)kvh * D * 2 + 4 * j * tok_bytes + r * 16;
+    const uint32_t page_bytes = kPageSize * tok_bytes;
+    const char *kc = (const char *)p.k_cache;
+    const char *vc = (const char *)p.v_cache;
     const int32_t *bt = p.block_table + (int64_t)b * p.max_pages;
     const int pg_end = (t1 + kPageSize - 1) / kPageSize;
 
+    // Two register buffers used alternately, so that the loads of page n+1 are
+    // in flight while page n is consumed.  A wave always issues the next load
+    // group, even past its last page (it then re-reads its last page, a cache
+    // hit), which keeps the number of loads in flight fixed and lets every wait
+    // be for "all but the newest group".
     int pg = t0 / kPageSize + wave;
-    PageRegs cur, nxt;
-    if (pg < pg_end)
-        load_page(cur, kc, vc, clamp_page(bt[pg], p.num_pages), Hkv, kvh, r, j);
-
-    for (; pg < pg_end; pg += kWaves) {
-        const bool more = pg + kWaves < pg_end;
-        if (more)
-            load_page(nxt, kc, vc, clamp_page(bt[pg + kWaves], p.num_pages), Hkv, kvh, r, j);
-
-        // ---- S = K Q^T
-        f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8, cur.k[kk]), __builtin_bit_cast(bf16x8, qb[kk]), s, 0, 0, 0);
-
-        const int tok = pg * kPageSize + 4 * j; // first of this lane's four tokens
-        const bool tail = pg * kPageSize + kPageSize > t1;
-        float sc[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            sc[i] = s[i] * p.scale_log2e;
-            if (tail && tok + i >= t1)
-                sc[i] = -INFINITY;
+    if (pg < pg_end) {
+        PageRegs A, B;
+        int page = clamp_page(bt[pg], p.num_pages);
+        load_page(A, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes), k_lane, v_lane,
+                  tok_bytes);
+        for (;;) {
+            if (pg + kWaves < pg_end)
+                page = clamp_page(bt[pg + kWaves], p.num_pages);
+            load_page(B, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes), k_lane,
+                      v_lane, tok_bytes);
+            attend_page(st, A, qb, p.scale_log2e, pg * kPageSize + 4 * j, t1, j);
+            pg += kWaves;
+            if (pg >= pg_end)
+                break;
+            if (pg + kWaves < pg_end)
+                page = clamp_page(bt[pg + kWaves], p.num_pages);
+            load_page(A, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes), k_lane,
+                      v_lane, tok_bytes);
+            attend_page(st, B, qb, p.scale_log2e, pg * kPageSize + 4 * j, t1, j);
+            pg += kWaves;
+            if (pg >= pg_end)
+                break;
         }
-        if (tail) { // rows of tokens past the end may hold anything: keep them out of P*V
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (tok + u >= t1)
-                    cur.v[u] = u32x4{0u, 0u, 0u, 0u};
-        }
-
-        // ---- online softmax
-        float bm = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-        bm = fmaxf(bm, __shfl_xor(bm, 16));
-        bm = fmaxf(bm, __shfl_xor(bm, 32));
-        if (__any(bm > m)) {
-            const float mn = fmaxf(m, bm);
-            const float alpha = fast_exp2(m - mn);
-            m = mn;
-            l *= alpha;
-            // O rows of this lane are heads 4j+i; their factors sit in lanes with r = 4j+i
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float a = __shfl(alpha, 4 * j + i);
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    o[e][i] *= a;
-            }
-        }
-        uint32_t ph[4], pl[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float pw = fast_exp2(sc[i] - m);
-            l += pw;
-            ph[i] = __float_as_uint(pw) & 0xffff0000u;                 // bf16 head (truncated)
-            pl[i] = __float_as_uint(pw - __uint_as_float(ph[i]));      // remainder, exact in fp32
-        }
-        u32x2 ah, al; // four bf16 each: element i <-> token 4j+i
-        ah[0] = (ph[0] >> 16) | ph[1];
-        ah[1] = (ph[2] >> 16) | ph[3];
-        al[0] = (pl[0] >> 16) | (pl[1] & 0xffff0000u);
-        al[1] = (pl[2] >> 16) | (pl[3] & 0xffff0000u);
-
-        // ---- O += P V
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-            u32x2 vb;
-            vb[0] = __builtin_amdgcn_perm(cur.v[1][e >> 1], cur.v[0][e >> 1], sel);
-            vb[1] = __builtin_amdgcn_perm(cur.v[3][e >> 1], cur.v[2][e >> 1], sel);
-            o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-                __builtin_bit_cast(s16x4, ah), __builtin_bit_cast(s16x4, vb), o[e], 0, 0, 0);
-            o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-                __builtin_bit_cast(s16x4, al), __builtin_bit_cast(s16x4, vb), o[e], 0, 0, 0);
-        }
-        if (more)
-            cur = nxt;
     }
 
     // denominators: sum the four lane groups
+    float l = st.l;
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
 
@@ -179,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
     float *sl = sm + kWaves * G;      // [kWaves][G]
     float *so = sl + kWaves * G;      // [kWaves][G][D]
     if (j == 0 && r < G) {
-        sm[wave * G + r] = m;
+        sm[wave * G + r] = st.m;
         sl[wave * G + r] = l;
     }
 #pragma unroll
@@ -188,7 +231,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
         if (g < G) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                so[(wave * G + g) * D + 8 * r + e] = o[e][i];
+                so[(wave * G + g) * D + 8 * r + e] = st.o[e][i];
         }
     }
     __syncthreads();
