@@ -6,11 +6,18 @@
 // Lane l is (r, j) = (l % 16, l / 16).
 //
 // QK^T  S[token][head] = K[16 x 128] * Q^T[128 x 16] as four
-//       v_mfma_f32_16x16x32_bf16.  The A operand (K) comes straight from
-//       global memory: lane (r, j) loads, for step kk, the 16 bytes of token r
-//       at chunk kk*4 + j -- the contraction index may be permuted freely as
-//       long as Q^T (the B operand, head r, loaded once) uses the same order.
-//       Heads r >= G are zero columns.
+//       v_mfma_f32_16x16x32_bf16.  The A operand wants lane (r, j) to hold 16
+//       bytes of token r -- sixteen different rows per quarter wave, a pattern
+//       the vector memory path serves one lane at a time.  So the K tile takes
+//       the coalesced route: four loads that each fetch four complete 256-byte
+//       rows and deposit them directly in LDS (no VGPRs), and the operand is
+//       then read from LDS.  Row t is stored with its sixteen 16-byte chunks
+//       XOR-permuted by t (slot s holds chunk s ^ t), which makes the operand
+//       reads -- sixteen rows, same chunk -- hit sixteen different bank groups.
+//       Step kk, lane (r, j) contracts chunk kk*4 + j; Q^T (the B operand,
+//       head r, loaded once) uses the same order.  Heads r >= G are zero
+//       columns.  Each wave owns two such tiles (the page being consumed and
+//       the page in flight).
 //       Result layout: lane (r, j) holds S[token 4j+i][head r], i = 0..3.
 // softmax  per lane over its 4 tokens, running max shared across the four
 //       lane groups j by two wave shuffles; fp32 throughout, base 2.
@@ -31,9 +38,11 @@ namespace adr {
 constexpr int D = 128;
 
 struct PageRegs {
-    u32x4 k[4]; // A operand pieces, step kk
     u32x4 v[4]; // natural rows, token 4j+u
 };
+
+constexpr int kTileBytes = kPageSize * D * 2; // one page of K for one kv-head
+constexpr int kStages = 2;
 
 // Buffer descriptor of one cache page: base = the page, range = the page's
 // bytes (reads past it return zero instead of touching memory), raw 32-bit
@@ -47,17 +56,30 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t page_rsrc(const char *cache, i
 }
 
 // Issue the eight 16-byte loads of one page (this lane's share of K and V for
-// one kv-head).
-__device__ __forceinline__ void load_page(PageRegs &pr, __amdgpu_buffer_rsrc_t krsrc,
-                                          __amdgpu_buffer_rsrc_t vrsrc, uint32_t k_lane,
+// one kv-head): four K loads that land in the LDS tile `ktile` (lane l of load
+// i fills bytes [i*1024 + 16 l, +16) of the tile), four V loads into registers.
+__device__ __forceinline__ void load_page(PageRegs &pr, char *ktile, __amdgpu_buffer_rsrc_t krsrc,
+                                          __amdgpu_buffer_rsrc_t vrsrc, const uint32_t (&k_lane)[4],
                                           uint32_t v_lane, uint32_t tok_bytes)
 {
+    asm volatile("" ::: "memory"); // earlier reads of this tile stay ahead of the loads that refill it
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-        pr.k[kk] = __builtin_amdgcn_raw_buffer_load_b128(krsrc, k_lane, kk * 64, 0);
+    for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (__attribute__((address_space(3))) void *)(ktile + i * 1024),
+                                                 16, k_lane[i], 0, 0, 0);
 #pragma unroll
     for (int u = 0; u < 4; ++u)
         pr.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrsrc, v_lane, u * tok_bytes, 0);
+    asm volatile("" ::: "memory");
+}
+
+// Wait until every vector-memory load except the newest group of eight has
+// completed.  Loads return in order, so the page issued before that group is
+// then whole: its K tile is in LDS (the compiler does not track loads that
+// write LDS, hence the explicit wait) and its V rows are in registers.
+__device__ __forceinline__ void wait_older_page()
+{
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
 }
 
 struct WaveState {
@@ -67,13 +89,18 @@ struct WaveState {
 };
 
 // One page: S = K Q^T, online softmax, O += P V.
-__device__ __forceinline__ void attend_page(WaveState &st, PageRegs &pg, const u32x4 (&qb)[4],
+__device__ __forceinline__ void attend_page(WaveState &st, PageRegs &pg, const char *ktile,
+                                            const uint32_t (&k_read)[4], const u32x4 (&qb)[4],
                                             float scale_log2e, int tok, int t1, int j)
 {
+    u32x4 ka[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        ka[kk] = *(const u32x4 *)(ktile + k_read[kk]);
     f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
-        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pg.k[kk]),
+        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kk]),
                                                     __builtin_bit_cast(bf16x8, qb[kk]), s, 0, 0, 0);
     // tok = index of the first of this lane's four tokens (4j + i)
     const bool tail = tok - 4 * j + kPageSize > t1;
@@ -171,54 +198,78 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
     st.m = kNegBig;
     st.l = 0.f;
 
-    // byte offsets of this lane inside a page: K: token r, chunk j (+ 4 per step); V: token 4j, chunk r
+    // Byte offsets of this lane.
+    //  K load i (to LDS): row t = 4i + j, slot r of that row, which holds chunk r ^ t.
+    //  K operand read, step kk: row r, chunk kk*4 + j, which sits in slot (kk*4 + j) ^ r.
+    //  V load u (to registers): row 4j + u, chunk r.
     const uint32_t tok_bytes = (uint32_t)Hkv * D * 2;
-    const uint32_t k_lane = (uint32_t)kvh * D * 2 + r * tok_bytes + j * 16;
+    uint32_t k_lane[4], k_read[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = 4 * i + j;
+        k_lane[i] = (uint32_t)kvh * D * 2 + t * tok_bytes + ((r ^ t) * 16);
+        k_read[i] = r * (D * 2) + (((i * 4 + j) ^ r) * 16);
+    }
     const uint32_t v_lane = (uint32_t)kvh * D * 2 + 4 * j * tok_bytes + r * 16;
     const uint32_t page_bytes = kPageSize * tok_bytes;
     const char *kc = (const char *)p.k_cache;
     const char *vc = (const char *)p.v_cache;
-    const int32_t *bt = p.block_table + (int64_t)b * p.max_pages;
+    // The block table is read through the constant address space: its entries are
+    // wave-uniform and never written while the kernel runs, so they arrive by
+    // scalar loads and stay out of the vector-memory counter the waits rely on.
+    typedef const __attribute__((address_space(4))) int32_t *table_ptr;
+    table_ptr bt = (table_ptr)(p.block_table + (int64_t)b * p.max_pages);
     const int pg_end = (t1 + kPageSize - 1) / kPageSize;
 
-    // Two register buffers used alternately, so that the loads of page n+1 are
-    // in flight while page n is consumed.  A wave always issues the next load
-    // group, even past its last page (it then re-reads its last page, a cache
-    // hit), which keeps the number of loads in flight fixed and lets every wait
-    // be for "all but the newest group".
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    char *tile0 = lds_raw + wave * (kStages * kTileBytes);
+    char *tile1 = tile0 + kTileBytes;
+
+    // Two page buffers used alternately (K tile in LDS + V rows in registers),
+    // so that the loads of page n+1 are in flight while page n is consumed.  A
+    // wave always issues the next load group, even past its last page (it then
+    // re-reads its last page, a cache hit), which keeps the number of loads in
+    // flight fixed: "all but the newest eight" is always the page to consume.
+    // Page ids are fetched two pages ahead.
     int pg = t0 / kPageSize + wave;
     if (pg < pg_end) {
         PageRegs A, B;
+        const int last = pg + (pg_end - 1 - pg) / kWaves * kWaves; // this wave's last page
         int page = clamp_page(bt[pg], p.num_pages);
-        load_page(A, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes), k_lane, v_lane,
-                  tok_bytes);
+        int page_next = clamp_page(bt[min(pg + kWaves, last)], p.num_pages);
+        load_page(A, tile0, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes), k_lane,
+                  v_lane, tok_bytes);
         for (;;) {
-            if (pg + kWaves < pg_end)
-                page = clamp_page(bt[pg + kWaves], p.num_pages);
-            load_page(B, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes), k_lane,
-                      v_lane, tok_bytes);
-            attend_page(st, A, qb, p.scale_log2e, pg * kPageSize + 4 * j, t1, j);
+            page = page_next;
+            page_next = clamp_page(bt[min(pg + 2 * kWaves, last)], p.num_pages);
+            load_page(B, tile1, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes),
+                      k_lane, v_lane, tok_bytes);
+            wait_older_page();
+            attend_page(st, A, tile0, k_read, qb, p.scale_log2e, pg * kPageSize + 4 * j, t1, j);
             pg += kWaves;
             if (pg >= pg_end)
                 break;
-            if (pg + kWaves < pg_end)
-                page = clamp_page(bt[pg + kWaves], p.num_pages);
-            load_page(A, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes), k_lane,
-                      v_lane, tok_bytes);
-            attend_page(st, B, qb, p.scale_log2e, pg * kPageSize + 4 * j, t1, j);
+            page = page_next;
+            page_next = clamp_page(bt[min(pg + 2 * kWaves, last)], p.num_pages);
+            load_page(A, tile0, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes),
+                      k_lane, v_lane, tok_bytes);
+            wait_older_page();
+            attend_page(st, B, tile1, k_read, qb, p.scale_log2e, pg * kPageSize + 4 * j, t1, j);
             pg += kWaves;
             if (pg >= pg_end)
                 break;
         }
     }
+    // the K tiles are dead from here on; the same LDS now carries the per-wave results
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
 
     // denominators: sum the four lane groups
     float l = st.l;
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
 
-    extern __shared__ float lds[];
-    float *sm = lds;                  // [kWaves][G]
+    float *sm = (float *)lds_raw;     // [kWaves][G]
     float *sl = sm + kWaves * G;      // [kWaves][G]
     float *so = sl + kWaves * G;      // [kWaves][G][D]
     if (j == 0 && r < G) {
@@ -243,7 +294,9 @@ hipError_t launch_decode_mfma(const DecodeParams &p, int d, hipStream_t stream)
     if (d != D)
         return hipErrorInvalidValue;
     const dim3 grid((unsigned)((int64_t)p.B * p.Hkv * p.max_parts));
-    const size_t lds = (size_t)kWaves * p.G * (D + 2) * sizeof(float);
+    size_t lds = (size_t)kWaves * p.G * (D + 2) * sizeof(float); // per-wave results
+    if (lds < (size_t)kWaves * kStages * kTileBytes)
+        lds = (size_t)kWaves * kStages * kTileBytes;             // K tiles
     decode_mfma_kernel<<<grid, kThreads, lds, stream>>>(p);
     return hipGetLastError();
 }
