@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libadr.so")
 
 ADR_BF16, ADR_FP8_E4M3, ADR_F32 = 0, 1, 2
-KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
+KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_MFMA_GRID = 0, 1, 2, 3
 PARTIALS_ONLY = 16
 
 EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention",

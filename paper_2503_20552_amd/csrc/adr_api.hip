@@ -7,6 +7,8 @@ namespace adr {
 hipError_t launch_kv_append(const AppendParams &p, bool fp8, hipStream_t stream);
 hipError_t launch_decode_valu(const DecodeParams &p, int d, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeParams &p, int d, hipStream_t stream);
+hipError_t launch_decode_stream(const DecodeParams &p, int d, hipStream_t stream);
+bool decode_stream_supports(int d, int G, int B);
 bool decode_valu_supports(int d, int G);
 bool decode_mfma_supports(int d, int G);
 hipError_t launch_lse_merge(const MergeParams &p, hipStream_t stream);
@@ -137,18 +139,23 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
     const bool fp8 = cache->dtype == ADR_FP8_E4M3;
     if (fp8)
         return ADR_ERR_UNSUPPORTED; // fp8 caches can be appended to but not attended yet
-    bool use_mfma;
+    enum { VALU, MFMA_GRID, MFMA_STREAM } kernel;
     if (want == ADR_KERNEL_VALU) {
         if (!adr::decode_valu_supports(d, G))
             return ADR_ERR_UNSUPPORTED;
-        use_mfma = false;
-    } else if (want == ADR_KERNEL_MFMA) {
+        kernel = VALU;
+    } else if (want == ADR_KERNEL_MFMA_GRID) {
         if (!adr::decode_mfma_supports(d, G))
             return ADR_ERR_UNSUPPORTED;
-        use_mfma = true;
-    } else if (want == ADR_KERNEL_AUTO) {
-        use_mfma = adr::decode_mfma_supports(d, G);
-        if (!use_mfma && !adr::decode_valu_supports(d, G))
+        kernel = MFMA_GRID;
+    } else if (want == ADR_KERNEL_MFMA || want == ADR_KERNEL_AUTO) {
+        if (adr::decode_stream_supports(d, G, B))
+            kernel = MFMA_STREAM;
+        else if (adr::decode_mfma_supports(d, G))
+            kernel = MFMA_GRID;
+        else if (want == ADR_KERNEL_AUTO && adr::decode_valu_supports(d, G))
+            kernel = VALU;
+        else
             return ADR_ERR_UNSUPPORTED;
     } else {
         return ADR_ERR_UNSUPPORTED;
@@ -197,8 +204,9 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
     p.out_f32 = out_dtype == ADR_F32;
     p.scale_log2e = scale * adr::kLog2e;
 
-    hipError_t e = use_mfma ? adr::launch_decode_mfma(p, d, (hipStream_t)stream)
-                            : adr::launch_decode_valu(p, d, (hipStream_t)stream);
+    hipError_t e = kernel == MFMA_STREAM ? adr::launch_decode_stream(p, d, (hipStream_t)stream)
+                   : kernel == MFMA_GRID ? adr::launch_decode_mfma(p, d, (hipStream_t)stream)
+                                         : adr::launch_decode_valu(p, d, (hipStream_t)stream);
     if (e != hipSuccess)
         return ADR_ERR_LAUNCH;
     if (split && !(flags & ADR_PARTIALS_ONLY)) {

@@ -1,0 +1,518 @@
+// Persistent matrix-core decode attention (d = 128, bf16 cache, G <= 16, B <= 512).
+//
+// The grid is a fixed number of workgroups (a couple per compute unit) that
+// stay resident and pull work items from a ticket counter until none is left.
+// An item is one (request, partition, kv-head); the four waves of a workgroup
+// share it, wave w streaming pages w, w+4, ... of the partition, exactly as in
+// decode_mfma.hip.  What changes is everything around the page loop:
+//
+//  * No empty workgroups.  Every workgroup first scans seq_lens into two
+//    prefix arrays in LDS (full partitions per row, ragged last partitions per
+//    row); ticket t is decoded by binary search.  Tickets enumerate all full
+//    partitions first and the ragged ones last, so the work that is handed out
+//    at the very end is the small pieces.
+//  * No pipeline drain between items.  A wave's page stream runs across item
+//    boundaries: while the last page of an item is consumed, the first page of
+//    the next item is already in flight, and the next item's query is loaded
+//    one item ahead.  Tickets are drawn two items ahead for that reason.
+//  * K and V tiles both arrive by direct-to-LDS loads into a two-stage ring
+//    per wave (K rows XOR-swizzled for the operand reads, V rows natural), so
+//    the ring position is a run-time value and the loop is not unrolled.
+//  * The query operand of an item is likewise staged in LDS (one 16-row tile per
+//    workgroup, fetched by wave 0 one item ahead), so no load into registers is
+//    ever pending inside the page loop and the compiler adds no waits there.
+//  * The cross-wave combination of an item reuses the ring stage that was
+//    consumed last as scratch; two barriers per item fence it.
+//
+// The ticket counter and a finished-workgroups counter live in a small pool of
+// static device words that are zero whenever no launch is using them: the last
+// workgroup to finish puts both back to zero.
+#include "mfma_page.h"
+
+#include <atomic>
+
+namespace adr {
+
+constexpr int kMaxStreamB = 512;
+constexpr int kTicketSlots = 64;
+constexpr int kRingBytes = kWaves * kStages * 2 * kTileBytes; // K and V tiles of all waves
+
+__device__ uint32_t g_tickets[kTicketSlots][2];
+
+struct StreamParams {
+    DecodeParams d;
+    uint32_t *ticket; // {next ticket, workgroups finished}
+    int pt;           // tokens per partition (2^30 when the pass is not split)
+};
+
+struct Item {
+    int valid;
+    int b, kvh, part;
+    int t1;      // end of the token range (exclusive); the range starts at part * pt
+    int n_parts; // partitions of the row (1: write the final result directly)
+    int pg;      // first page of this wave
+    int pg_end;  // one past the last page of the item
+};
+
+typedef const __attribute__((address_space(4))) int32_t *table_ptr;
+
+constexpr int kQTileBytes = 16 * D * 2; // sixteen query rows (heads of a group, zero beyond G)
+
+// LDS layout behind the ring
+struct Shared {
+    char qtile[2][kQTileBytes]; // query tile of the current / the next item, rows swizzled like K
+    float ml[kWaves][16][2]; // per wave: running max, denominator of each head
+    int stage_off[kWaves];   // byte offset of the ring stage a wave used as scratch
+    int slot[2];             // tickets of the items after the current one
+    int wave_tot[2][kWaves];
+    int total[2];
+    int pref_full[kMaxStreamB + 1];
+    int pref_rag[kMaxStreamB + 1];
+    int len[kMaxStreamB];
+};
+
+// largest b with pref[b] <= u  (pref is an exclusive prefix sum of length B+1)
+__device__ __forceinline__ int find_row(const int *pref, int B, int u)
+{
+    int lo = 0, hi = B; // invariant: pref[lo] <= u < pref[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (__builtin_amdgcn_readfirstlane(pref[mid]) <= u)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamParams &sp, int ticket,
+                                              int wave)
+{
+    Item it;
+    const int Hkv = sp.d.Hkv, B = sp.d.B;
+    // everything below is the same in all lanes; say so, to keep it in scalar registers
+    ticket = __builtin_amdgcn_readfirstlane(ticket);
+    const int total_full = __builtin_amdgcn_readfirstlane(sh.total[0]);
+    const int total_rag = __builtin_amdgcn_readfirstlane(sh.total[1]);
+    it.valid = ticket < (total_full + total_rag) * Hkv;
+    it.b = it.kvh = it.part = it.t1 = it.pg = it.pg_end = 0;
+    it.n_parts = 1;
+    if (it.valid) {
+        const int unit = ticket / Hkv;
+        it.kvh = ticket - unit * Hkv;
+        int b, t1;
+        if (unit < total_full) {
+            b = find_row(sh.pref_full, B, unit);
+            it.part = unit - sh.pref_full[b];
+            t1 = (it.part + 1) * sp.pt;
+        } else {
+            b = find_row(sh.pref_rag, B, unit - total_full);
+            it.part = sh.pref_full[b + 1] - sh.pref_full[b];
+            t1 = sh.len[b];
+        }
+        const int L = sh.len[b];
+        it.b = __builtin_amdgcn_readfirstlane(b);
+        it.part = __builtin_amdgcn_readfirstlane(it.part);
+        it.kvh = __builtin_amdgcn_readfirstlane(it.kvh);
+        it.t1 = __builtin_amdgcn_readfirstlane(t1);
+        const int np = L > 0 ? (L - 1) / sp.pt + 1 : 1;
+        it.n_parts = __builtin_amdgcn_readfirstlane(np);
+        // part * pt cannot overflow: when the pass is not split, part is 0
+        it.pg = it.part * (sp.pt / kPageSize) + wave;
+        it.pg_end = (it.t1 + kPageSize - 1) / kPageSize;
+    }
+    return it;
+}
+
+// Fetch the query tile of one item into LDS (one wave calls this): sixteen rows
+// of 256 bytes, row t stored with its chunks XOR-permuted by t exactly like a K
+// tile.  The descriptor spans the G rows of the group; rows beyond it are out of
+// range (their content is never used: they only feed score columns >= G).
+__device__ __forceinline__ void issue_query(char *qtile, const StreamParams &sp, const Item &it,
+                                            const uint32_t (&q_lane)[4])
+{
+    const char *base = (const char *)(sp.d.q + (int64_t)it.b * sp.d.q_row_stride +
+                                      (int64_t)it.kvh * sp.d.G * D);
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, it.valid ? sp.d.G * D * 2 : 0, 0x00020000);
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rs, (__attribute__((address_space(3))) void *)(qtile + i * 1024), 16, q_lane[i], 0, 0, 0);
+    asm volatile("" ::: "memory");
+}
+
+// Eight direct-to-LDS loads: K rows (swizzled) then V rows (natural) of one page
+// for one kv-head into ring stage `tile` (K tile, then V tile).
+__device__ __forceinline__ void issue_page(char *tile, __amdgpu_buffer_rsrc_t krsrc,
+                                           __amdgpu_buffer_rsrc_t vrsrc, const uint32_t (&k_lane)[4],
+                                           const uint32_t (&v_lane)[4], uint32_t head_bytes)
+{
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            krsrc, (__attribute__((address_space(3))) void *)(tile + i * 1024), 16, k_lane[i],
+            head_bytes, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            vrsrc, (__attribute__((address_space(3))) void *)(tile + kTileBytes + i * 1024), 16,
+            v_lane[i], head_bytes, 0, 0);
+    asm volatile("" ::: "memory");
+}
+
+// Workgroup barrier for the item loop: orders this wave's LDS accesses (they
+// complete in issue order once the LDS counter has drained) without waiting for
+// the direct-to-LDS page loads still in flight, which target a ring stage that
+// no other wave ever touches.
+__device__ __forceinline__ void ring_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void decode_stream_kernel(const StreamParams sp)
+{
+    const DecodeParams &p = sp.d;
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    Shared &sh = *(Shared *)(lds_raw + kRingBytes);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15;
+    const int j = lane >> 4;
+    const int B = p.B, Hkv = p.Hkv, G = p.G;
+
+    // ---- partitions per row: exclusive prefix sums over the rows, four rows per thread
+    {
+        int f[4], g[4], sf = 0, sg = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = tid * 4 + i;
+            int L = 0;
+            f[i] = g[i] = 0;
+            if (row < B) {
+                L = max(min(p.seq_lens[row], p.max_seq_len), 0);
+                sh.len[row] = L;
+                f[i] = L / sp.pt;
+                g[i] = (L % sp.pt != 0 || L == 0) ? 1 : 0; // an empty row still owns one (empty) item
+            }
+            sf += f[i];
+            sg += g[i];
+        }
+        int xf = sf, xg = sg; // inclusive scan over the lanes of the wave
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int yf = __shfl_up(xf, off), yg = __shfl_up(xg, off);
+            if (lane >= off) {
+                xf += yf;
+                xg += yg;
+            }
+        }
+        if (lane == 63) {
+            sh.wave_tot[0][wave] = xf;
+            sh.wave_tot[1][wave] = xg;
+        }
+        __syncthreads();
+        int bf = 0, bg = 0, tf = 0, tg = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            if (w < wave) {
+                bf += sh.wave_tot[0][w];
+                bg += sh.wave_tot[1][w];
+            }
+            tf += sh.wave_tot[0][w];
+            tg += sh.wave_tot[1][w];
+        }
+        int ef = bf + xf - sf, eg = bg + xg - sg;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = tid * 4 + i;
+            if (row < B) {
+                sh.pref_full[row] = ef;
+                sh.pref_rag[row] = eg;
+            }
+            ef += f[i];
+            eg += g[i];
+        }
+        if (tid == 0) {
+            sh.pref_full[B] = tf;
+            sh.pref_rag[B] = tg;
+            sh.total[0] = tf;
+            sh.total[1] = tg;
+            sh.slot[0] = (int)atomicAdd(sp.ticket, 1u);
+            sh.slot[1] = (int)atomicAdd(sp.ticket, 1u);
+        }
+        __syncthreads();
+    }
+
+    // ---- per-lane constants
+    const uint32_t tok_bytes = (uint32_t)Hkv * D * 2;
+    const uint32_t page_bytes = kPageSize * tok_bytes;
+    uint32_t k_lane[4], v_lane[4], q_lane[4], k_read[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = 4 * i + j;                       // row this lane fetches in load i
+        k_lane[i] = t * tok_bytes + ((r ^ t) * 16);     // slot r of row t holds chunk r ^ t
+        v_lane[i] = t * tok_bytes + r * 16;
+        q_lane[i] = t * (D * 2) + ((r ^ t) * 16);
+        k_read[i] = r * (D * 2) + (((i * 4 + j) ^ r) * 16);
+    }
+    const uint32_t v_read = (4 * j) * (D * 2) + r * 16; // row 4j (+u), chunk r
+    const char *kc = (const char *)p.k_cache;
+    const char *vc = (const char *)p.v_cache;
+    char *ring = lds_raw + wave * (kStages * 2 * kTileBytes);
+    const __amdgpu_buffer_rsrc_t null_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)kc, 0, 0, 0x00020000); // every read is out of range: zeros
+
+    Item C = decode_ticket(sh, sp, sh.slot[0], wave);
+    Item N = decode_ticket(sh, sp, sh.slot[1], wave);
+    if (wave == 0) {
+        issue_query(sh.qtile[0], sp, C, q_lane);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();
+
+    // ---- load cursor: the next page of this wave's stream to be issued.  It runs
+    // through the current item and on into the next one, never further.  It keeps
+    // its own copy of what it needs from the item it is in.
+    int ld_in_next = 0;
+    int ld_pg = C.pg, ld_end = C.valid ? C.pg_end : 0;
+    uint32_t ld_head = (uint32_t)C.kvh * (D * 2);
+    table_ptr ld_bt = (table_ptr)(p.block_table + (int64_t)C.b * p.max_pages);
+    int ld_ok = 0, ld_id = 0;
+#define ADR_SETTLE()                                                                              \
+    do { /* move the cursor to the next existing page and fetch its page id */                    \
+        if (!ld_in_next && ld_pg >= ld_end) {                                                     \
+            ld_in_next = 1;                                                                       \
+            ld_pg = N.pg;                                                                         \
+            ld_end = N.valid ? N.pg_end : 0;                                                      \
+            ld_head = (uint32_t)N.kvh * (D * 2);                                                  \
+            ld_bt = (table_ptr)(p.block_table + (int64_t)N.b * p.max_pages);                      \
+        }                                                                                         \
+        ld_ok = ld_pg < ld_end;                                                                   \
+        if (ld_ok)                                                                                \
+            ld_id = clamp_page(ld_bt[ld_pg], p.num_pages);                                        \
+    } while (0)
+#define ADR_ISSUE(STAGE)                                                                          \
+    do { /* issue the cursor's page, or a group of null loads, into a ring stage */               \
+        char *tile_ = ring + (STAGE) * (2 * kTileBytes);                                          \
+        if (ld_ok) {                                                                              \
+            issue_page(tile_, page_rsrc(kc, ld_id, page_bytes), page_rsrc(vc, ld_id, page_bytes), \
+                       k_lane, v_lane, ld_head);                                                  \
+            ld_pg += kWaves;                                                                      \
+            ADR_SETTLE();                                                                         \
+        } else {                                                                                  \
+            issue_page(tile_, null_rsrc, null_rsrc, k_lane, v_lane, 0);                           \
+        }                                                                                         \
+    } while (0)
+    ADR_SETTLE();
+    int stage = 0;
+    if (ld_ok && !ld_in_next)
+        ADR_ISSUE(stage); // first page of the first item
+
+    uint32_t next_ticket = 0;
+    // Drawn once per item, after the item's first page has been consumed (so that
+    // nothing at the top of an item waits for these round trips): the ticket of the
+    // item after N, and N's query.
+#define ADR_LOOK_AHEAD()                                                                          \
+    do {                                                                                          \
+        if (tid == 0)                                                                             \
+            asm volatile("global_atomic_add %0, %1, %2, %3 sc0"                                   \
+                         : "=&v"(next_ticket)                                                     \
+                         : "v"(0), "v"(1), "s"(sp.ticket)                                         \
+                         : "memory");                                                             \
+        if (wave == 0)                                                                            \
+            issue_query(sh.qtile[(k + 1) & 1], sp, N, q_lane);                                    \
+    } while (0)
+
+    for (int k = 0; C.valid; ++k) {
+        WaveState st;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            st.o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+        st.m = kNegBig;
+        st.l = 0.f;
+        u32x4 qb[4]; // B operand of QK^T: head r's query, chunk order matching the K reads
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            qb[kk] = *(const u32x4 *)(sh.qtile[k & 1] + k_read[kk]);
+
+        const bool ran = C.pg < C.pg_end;
+        for (int pg = C.pg; pg < C.pg_end; pg += kWaves) {
+            ADR_ISSUE(stage ^ 1);
+            wait_older_page();
+            const char *tile = ring + stage * (2 * kTileBytes);
+            PageRegs pr;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                pr.v[u] = *(const u32x4 *)(tile + kTileBytes + v_read + u * (D * 2));
+            attend_page(st, pr, tile, k_read, qb, p.scale_log2e, pg * kPageSize + 4 * j, C.t1, j);
+            stage ^= 1;
+            if (pg == C.pg)
+                ADR_LOOK_AHEAD();
+        }
+        if (!ran)
+            ADR_LOOK_AHEAD();
+        // `stage` now names the ring stage that receives the next item's first page:
+        // issued by the last iteration above, or here when this wave had no page.
+        if (!ran && ld_ok && ld_in_next)
+            ADR_ISSUE(stage);
+
+        // ---- combine the four waves; scratch = the stage not being filled
+        float l = st.l;
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const int scratch_off = wave * (kStages * 2 * kTileBytes) + (stage ^ 1) * (2 * kTileBytes);
+        // The scratch stage has no load in flight: every group that targeted it was
+        // waited for before its page was consumed.  Wave 0 needs the ticket it drew
+        // and the query tile it requested after the item's first page: at least one
+        // load group has been issued since if the wave had a second page, otherwise
+        // everything is waited for.
+        if (wave == 0) {
+            if (C.pg + kWaves < C.pg_end)
+                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            else
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        float *so = (float *)(lds_raw + scratch_off); // [G][D]
+        if (j == 0 && r < G) {
+            sh.ml[wave][r][0] = st.m;
+            sh.ml[wave][r][1] = l;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int g = 4 * j + i;
+            if (g < G) {
+                *(f32x4 *)(so + g * D + 8 * r) = f32x4{st.o[0][i], st.o[1][i], st.o[2][i], st.o[3][i]};
+                *(f32x4 *)(so + g * D + 8 * r + 4) = f32x4{st.o[4][i], st.o[5][i], st.o[6][i], st.o[7][i]};
+            }
+        }
+        if (lane == 0)
+            sh.stage_off[wave] = scratch_off;
+        if (tid == 0)
+            sh.slot[k & 1] = (int)next_ticket;
+        ring_barrier();
+
+        for (int idx = tid; idx < G * D; idx += kThreads) {
+            const int g = idx / D, dd = idx - g * D;
+            float M = sh.ml[0][g][0];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w)
+                M = fmaxf(M, sh.ml[w][g][0]);
+            float acc = 0.f, den = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const float f = fast_exp2(sh.ml[w][g][0] - M);
+                acc += f * ((const float *)(lds_raw + sh.stage_off[w]))[g * D + dd];
+                den += f * sh.ml[w][g][1];
+            }
+            const float o = den > 0.f ? acc / den : 0.f;
+            const float lse = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
+            const int h = C.kvh * G + g;
+            if (C.n_parts == 1) {
+                const int64_t off = ((int64_t)C.b * p.Hq + h) * D + dd;
+                if (p.out_f32)
+                    ((float *)p.out)[off] = o;
+                else
+                    ((uint16_t *)p.out)[off] = (uint16_t)f32_to_bf16(o);
+                if (p.lse && dd == 0)
+                    p.lse[(int64_t)C.b * p.Hq + h] = lse;
+            } else {
+                const int64_t row = ((int64_t)C.b * p.max_parts + C.part) * p.Hq + h;
+                p.part_o[row * D + dd] = o;
+                if (dd == 0)
+                    p.part_lse[row] = lse;
+            }
+        }
+        const int following = sh.slot[k & 1];
+        ring_barrier(); // scratch stages and the ticket slot are free again
+
+        // ---- next item becomes current
+        C = N;
+        N = decode_ticket(sh, sp, following, wave);
+        // The cursor is always inside the item that has just become current (issuing
+        // the last page of an item moves it on, and so does an item without pages).
+        ld_in_next = 0;
+        if (!ld_ok)
+            ADR_SETTLE(); // it had run out of pages there: move on into the new next item
+    }
+
+#undef ADR_LOOK_AHEAD
+#undef ADR_ISSUE
+#undef ADR_SETTLE
+
+    // ---- hand the counters back to zero once every workgroup is through
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (tid == 0) {
+        const uint32_t done = atomicAdd(sp.ticket + 1, 1u);
+        if (done == gridDim.x - 1) {
+            atomicExch(sp.ticket, 0u);
+            atomicExch(sp.ticket + 1, 0u);
+        }
+    }
+}
+
+namespace {
+std::atomic<unsigned> g_next_slot{0};
+}
+
+// Switched off: the first run of this kernel on the GPU ended in a memory fault
+// whose cause has not been found yet, so no entry point dispatches to it.
+constexpr bool kStreamKernelEnabled = false;
+
+bool decode_stream_supports(int d, int G, int B)
+{
+    return kStreamKernelEnabled && d == D && G >= 1 && G <= 16 && B <= kMaxStreamB;
+}
+
+hipError_t launch_decode_stream(const DecodeParams &p, int d, hipStream_t stream)
+{
+    if (!decode_stream_supports(d, p.G, p.B))
+        return hipErrorInvalidValue;
+    // per-device set-up, once: address of the counter pool, LDS limit, grid size
+    struct DeviceInfo {
+        uint32_t *tickets = nullptr;
+        int workgroups = 0;
+    };
+    static DeviceInfo info[64];
+    static std::atomic<int> ready[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= 64)
+        return hipErrorInvalidDevice;
+    const size_t lds = kRingBytes + sizeof(Shared);
+    if (!ready[dev].load(std::memory_order_acquire)) {
+        DeviceInfo di;
+        if ((e = hipGetSymbolAddress((void **)&di.tickets, HIP_SYMBOL(g_tickets))) != hipSuccess)
+            return e;
+        if ((e = hipFuncSetAttribute((const void *)decode_stream_kernel,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
+            return e;
+        int cus = 0, per_cu = 0;
+        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess)
+            return e;
+        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel, kThreads,
+                                                              lds)) != hipSuccess)
+            return e;
+        if (per_cu < 1)
+            per_cu = 1;
+        di.workgroups = cus * per_cu;
+        info[dev] = di;
+        ready[dev].store(1, std::memory_order_release);
+    }
+    StreamParams sp;
+    sp.d = p;
+    sp.ticket = info[dev].tickets + 2 * (g_next_slot.fetch_add(1) % kTicketSlots);
+    sp.pt = p.partition_tokens > 0 ? p.partition_tokens : (1 << 30);
+    int64_t grid = (int64_t)p.B * p.Hkv * p.max_parts;
+    if (grid > info[dev].workgroups)
+        grid = info[dev].workgroups;
+    decode_stream_kernel<<<dim3((unsigned)grid), kThreads, lds, stream>>>(sp);
+    return hipGetLastError();
+}
+
+} // namespace adr

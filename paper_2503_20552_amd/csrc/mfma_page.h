@@ -1,0 +1,138 @@
+// Pieces shared by the two matrix-core decode kernels (d = 128, bf16 cache):
+// per-page buffer descriptors, the K tile's LDS layout, and the per-page
+// arithmetic S = K Q^T -> online softmax -> O += P V.  See decode_mfma.hip for
+// the operand layouts.
+#pragma once
+
+#include "adr_device.h"
+
+namespace adr {
+
+constexpr int D = 128;
+
+struct PageRegs {
+    u32x4 v[4]; // natural rows, token 4j+u
+};
+
+constexpr int kTileBytes = kPageSize * D * 2; // one page of K for one kv-head
+constexpr int kStages = 2;
+
+// Buffer descriptor of one cache page: base = the page, range = the page's
+// bytes (reads past it return zero instead of touching memory), raw 32-bit
+// addressing.  Built from wave-uniform values, so it lives in scalar registers
+// and every load is "descriptor + 32-bit lane offset + scalar offset".
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t page_rsrc(const char *cache, int page,
+                                                            uint32_t page_bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)(cache + (size_t)page * page_bytes), 0,
+                                             (int)page_bytes, 0x00020000);
+}
+
+// Issue the eight 16-byte loads of one page (this lane's share of K and V for
+// one kv-head): four K loads that land in the LDS tile `ktile` (lane l of load
+// i fills bytes [i*1024 + 16 l, +16) of the tile), four V loads into registers.
+__device__ __forceinline__ void load_page(PageRegs &pr, char *ktile, __amdgpu_buffer_rsrc_t krsrc,
+                                          __amdgpu_buffer_rsrc_t vrsrc, const uint32_t (&k_lane)[4],
+                                          uint32_t v_lane, uint32_t tok_bytes)
+{
+    asm volatile("" ::: "memory"); // earlier reads of this tile stay ahead of the loads that refill it
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (__attribute__((address_space(3))) void *)(ktile + i * 1024),
+                                                 16, k_lane[i], 0, 0, 0);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        pr.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrsrc, v_lane, u * tok_bytes, 0);
+    asm volatile("" ::: "memory");
+}
+
+// Wait until every vector-memory load except the newest group of eight has
+// completed.  Loads return in order, so the page issued before that group is
+// then whole: its K tile is in LDS (the compiler does not track loads that
+// write LDS, hence the explicit wait) and its V rows are in registers.
+__device__ __forceinline__ void wait_older_page()
+{
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+}
+
+struct WaveState {
+    f32x4 o[8]; // O[head 4j+i][8r+e]
+    float m;    // running max of head r (same value in all four lane groups)
+    float l;    // this lane's share of head r's denominator
+};
+
+// One page: S = K Q^T, online softmax, O += P V.
+__device__ __forceinline__ void attend_page(WaveState &st, PageRegs &pg, const char *ktile,
+                                            const uint32_t (&k_read)[4], const u32x4 (&qb)[4],
+                                            float scale_log2e, int tok, int t1, int j)
+{
+    u32x4 ka[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        ka[kk] = *(const u32x4 *)(ktile + k_read[kk]);
+    f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kk]),
+                                                    __builtin_bit_cast(bf16x8, qb[kk]), s, 0, 0, 0);
+    // tok = index of the first of this lane's four tokens (4j + i)
+    const bool tail = tok - 4 * j + kPageSize > t1;
+    float sc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        sc[i] = s[i] * scale_log2e;
+        if (tail && tok + i >= t1)
+            sc[i] = -INFINITY;
+    }
+    if (tail) { // rows of tokens past the end may hold anything: keep them out of P*V
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (tok + u >= t1)
+                pg.v[u] = u32x4{0u, 0u, 0u, 0u};
+    }
+
+    float bm = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+    bm = fmaxf(bm, __shfl_xor(bm, 16));
+    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    if (__any(bm > st.m)) {
+        const float mn = fmaxf(st.m, bm);
+        const float alpha = fast_exp2(st.m - mn);
+        st.m = mn;
+        st.l *= alpha;
+        // O rows of this lane are heads 4j+i; their factors sit in lanes with r = 4j+i
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float a = __shfl(alpha, 4 * j + i);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                st.o[e][i] *= a;
+        }
+    }
+    uint32_t ph[4], pl[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float pw = fast_exp2(sc[i] - st.m);
+        st.l += pw;
+        ph[i] = __float_as_uint(pw) & 0xffff0000u;            // bf16 head (truncated)
+        pl[i] = __float_as_uint(pw - __uint_as_float(ph[i])); // remainder, exact in fp32
+    }
+    u32x2 ah, al; // four bf16 each: element i <-> token 4j+i
+    ah[0] = (ph[0] >> 16) | ph[1];
+    ah[1] = (ph[2] >> 16) | ph[3];
+    al[0] = (pl[0] >> 16) | (pl[1] & 0xffff0000u);
+    al[1] = (pl[2] >> 16) | (pl[3] & 0xffff0000u);
+
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        u32x2 vb;
+        vb[0] = __builtin_amdgcn_perm(pg.v[1][e >> 1], pg.v[0][e >> 1], sel);
+        vb[1] = __builtin_amdgcn_perm(pg.v[3][e >> 1], pg.v[2][e >> 1], sel);
+        st.o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+            __builtin_bit_cast(s16x4, ah), __builtin_bit_cast(s16x4, vb), st.o[e], 0, 0, 0);
+        st.o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+            __builtin_bit_cast(s16x4, al), __builtin_bit_cast(s16x4, vb), st.o[e], 0, 0, 0);
+    }
+}
+
+} // namespace adr

@@ -15,7 +15,8 @@ from gpu_util import ATOL, compare, dev, gpu_attention, oracle_attention, say
 
 pytestmark = pytest.mark.gpu
 
-KERNELS = {"valu": adr.KERNEL_VALU, "mfma": adr.KERNEL_MFMA, "auto": adr.KERNEL_AUTO}
+KERNELS = {"valu": adr.KERNEL_VALU, "mfma": adr.KERNEL_MFMA, "grid": adr.KERNEL_MFMA_GRID,
+           "auto": adr.KERNEL_AUTO}
 
 
 def small_case(seed, Hq, Hkv, d, lens, pool_pages=0):
@@ -90,12 +91,12 @@ def test_append_from_a_grouped_qkv_buffer():
 LENS = [1, 2, 15, 16, 17, 31, 33, 63, 64, 65, 100, 257, 512, 513, 1000, 1499]
 
 
-@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+@pytest.mark.parametrize("kernel", ["valu", "mfma", "grid"])
 @pytest.mark.parametrize("Hq,Hkv,d", [(8, 8, 128), (8, 2, 128), (8, 1, 128), (32, 8, 128),
                                       (4, 2, 128), (8, 8, 64), (8, 2, 64), (16, 2, 64)])
 @pytest.mark.parametrize("partition_tokens", [0, 64, 512])
 def test_attention_matches_oracle(kernel, Hq, Hkv, d, partition_tokens):
-    if kernel == "mfma" and d != 128:
+    if kernel in ("mfma", "grid") and d != 128:
         pytest.skip("the matrix-core kernel covers d = 128")
     b = small_case(10 + Hq + Hkv, Hq, Hkv, d, [L - 1 for L in LENS] + [0])
     seq = b.seq_lens.copy()
@@ -109,7 +110,7 @@ def test_attention_matches_oracle(kernel, Hq, Hkv, d, partition_tokens):
     assert torch.all(out[-1] == 0) and torch.isneginf(lse[-1]).all()
 
 
-@pytest.mark.parametrize("kernel", ["mfma"])
+@pytest.mark.parametrize("kernel", ["mfma", "grid"])
 def test_groups_up_to_sixteen_on_the_matrix_cores(kernel):
     b = small_case(40, 32, 2, 128, [0, 16, 90, 700])
     say("G=16 mfma")
@@ -129,7 +130,7 @@ def test_bf16_output_is_the_rounded_fp32_output():
         assert torch.equal(o32.to(torch.bfloat16), o16)
 
 
-@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+@pytest.mark.parametrize("kernel", ["valu", "mfma", "grid"])
 def test_run_to_run_and_page_placement_invariance(kernel):
     b = small_case(42, 8, 2, 128, [700, 33, 1200, 5])
     table = dev(b.block_table); seq = dev(b.seq_lens); q = dev(b.q)
