@@ -94,7 +94,7 @@ __device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamPara
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     const int total_full = __builtin_amdgcn_readfirstlane(sh.total[0]);
     const int total_rag = __builtin_amdgcn_readfirstlane(sh.total[1]);
-    it.valid = ticket < (total_full + total_rag) * Hkv;
+    it.valid = (unsigned)ticket < (unsigned)((total_full + total_rag) * Hkv);
     it.b = it.kvh = it.part = it.t1 = it.pg = it.pg_end = 0;
     it.n_parts = 1;
     if (it.valid) {
@@ -317,11 +317,14 @@ void decode_stream_kernel(const StreamParams sp)
     uint32_t next_ticket = 0;
     // Drawn once per item, after the item's first page has been consumed (so that
     // nothing at the top of an item waits for these round trips): the ticket of the
-    // item after N, and N's query.
+    // item after N, and N's query.  The counter's address may reach its scalar
+    // registers through a vector-lane read just before the statement; the five
+    // wait states such a value needs before a memory instruction may use it are
+    // not inserted around hand-written instructions, hence the s_nop.
 #define ADR_LOOK_AHEAD()                                                                          \
     do {                                                                                          \
         if (tid == 0)                                                                             \
-            asm volatile("global_atomic_add %0, %1, %2, %3 sc0"                                   \
+            asm volatile("s_nop 4\n\tglobal_atomic_add %0, %1, %2, %3 sc0"                        \
                          : "=&v"(next_ticket)                                                     \
                          : "v"(0), "v"(1), "s"(sp.ticket)                                         \
                          : "memory");                                                             \
@@ -460,9 +463,7 @@ namespace {
 std::atomic<unsigned> g_next_slot{0};
 }
 
-// Switched off: the first run of this kernel on the GPU ended in a memory fault
-// whose cause has not been found yet, so no entry point dispatches to it.
-constexpr bool kStreamKernelEnabled = false;
+constexpr bool kStreamKernelEnabled = true;
 
 bool decode_stream_supports(int d, int G, int B)
 {
