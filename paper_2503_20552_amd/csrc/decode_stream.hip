@@ -15,14 +15,21 @@
 //    boundaries: while the last page of an item is consumed, the first page of
 //    the next item is already in flight, and the next item's query is loaded
 //    one item ahead.  Tickets are drawn two items ahead for that reason.
-//  * K and V tiles both arrive by direct-to-LDS loads into a two-stage ring
-//    per wave (K rows XOR-swizzled for the operand reads, V rows natural), so
-//    the ring position is a run-time value and the loop is not unrolled.
+//  * K and V tiles both arrive by direct-to-LDS loads into a ring of S stages per
+//    wave (K rows XOR-swizzled for the operand reads, V rows natural); S - 1
+//    pages are in flight while one is consumed.  One workgroup per compute
+//    unit owns (almost) its whole LDS, which is what pays for the deep ring:
+//    the loads in flight keep the memory pipes fed while the waves of the
+//    workgroup meet at an item's end.  The ring position is a run-time value.
+//    A wave whose stream has run dry (no further page in the current or the
+//    next item) fills ring slots with null loads, so the number of load groups
+//    in flight never changes and one wait count serves every page; null slots
+//    are skipped when their turn comes.
 //  * The query operand of an item is likewise staged in LDS (one 16-row tile per
 //    workgroup, fetched by wave 0 one item ahead), so no load into registers is
 //    ever pending inside the page loop and the compiler adds no waits there.
-//  * The cross-wave combination of an item reuses the ring stage that was
-//    consumed last as scratch; two barriers per item fence it.
+//  * The cross-wave combination of an item goes through a double-buffered
+//    staging area, so one barrier per item is enough.
 //
 // The ticket counter and a finished-workgroups counter live in a small pool of
 // static device words that are zero whenever no launch is using them: the last
@@ -35,7 +42,7 @@ namespace adr {
 
 constexpr int kMaxStreamB = 512;
 constexpr int kTicketSlots = 64;
-constexpr int kRingBytes = kWaves * kStages * 2 * kTileBytes; // K and V tiles of all waves
+constexpr int kStageBytes = 2 * kTileBytes; // one ring stage: K tile, then V tile
 
 __device__ uint32_t g_tickets[kTicketSlots][2];
 
@@ -43,6 +50,7 @@ struct StreamParams {
     DecodeParams d;
     uint32_t *ticket; // {next ticket, workgroups finished}
     int pt;           // tokens per partition (2^30 when the pass is not split)
+    int stages;       // ring stages per wave (2..4)
 };
 
 struct Item {
@@ -56,14 +64,15 @@ struct Item {
 
 typedef const __attribute__((address_space(4))) int32_t *table_ptr;
 
+constexpr int kMaxLdsBytes = 160 * 1024;  // LDS of one compute unit
 constexpr int kQTileBytes = 16 * D * 2; // sixteen query rows (heads of a group, zero beyond G)
 
-// LDS layout behind the ring
+// LDS layout: the ring (kWaves * stages * kStageBytes), this block, then the
+// staging area float[2][kWaves][G][D] for the per-wave results of an item.
 struct Shared {
     char qtile[2][kQTileBytes]; // query tile of the current / the next item, rows swizzled like K
-    float ml[kWaves][16][2]; // per wave: running max, denominator of each head
-    int stage_off[kWaves];   // byte offset of the ring stage a wave used as scratch
-    int slot[2];             // tickets of the items after the current one
+    float ml[2][kWaves][16][2]; // per item parity, per wave: running max, denominator of each head
+    int slot[2];                // tickets of the items after the current one
     int wave_tot[2][kWaves];
     int total[2];
     int pref_full[kMaxStreamB + 1];
@@ -165,19 +174,33 @@ __device__ __forceinline__ void issue_page(char *tile, __amdgpu_buffer_rsrc_t kr
 
 // Workgroup barrier for the item loop: orders this wave's LDS accesses (they
 // complete in issue order once the LDS counter has drained) without waiting for
-// the direct-to-LDS page loads still in flight, which target a ring stage that
+// the direct-to-LDS page loads still in flight, which target ring stages that
 // no other wave ever touches.
 __device__ __forceinline__ void ring_barrier()
 {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// Wait until all but the newest S - 1 load groups (of eight loads) have landed.
+__device__ __forceinline__ void wait_ring(int stages)
+{
+    if (stages == 4)
+        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+    else if (stages == 3)
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+}
+
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 2)))
 void decode_stream_kernel(const StreamParams sp)
 {
     const DecodeParams &p = sp.d;
+    const int S = sp.stages;
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    Shared &sh = *(Shared *)(lds_raw + kRingBytes);
+    const int ring_bytes = kWaves * S * kStageBytes;
+    Shared &sh = *(Shared *)(lds_raw + ring_bytes);
+    float *staging = (float *)(lds_raw + ring_bytes + sizeof(Shared)); // [2][kWaves][G][D]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -264,7 +287,7 @@ void decode_stream_kernel(const StreamParams sp)
     const uint32_t v_read = (4 * j) * (D * 2) + r * 16; // row 4j (+u), chunk r
     const char *kc = (const char *)p.k_cache;
     const char *vc = (const char *)p.v_cache;
-    char *ring = lds_raw + wave * (kStages * 2 * kTileBytes);
+    char *ring = lds_raw + wave * (S * kStageBytes);
     const __amdgpu_buffer_rsrc_t null_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)kc, 0, 0, 0x00020000); // every read is out of range: zeros
 
@@ -298,21 +321,26 @@ void decode_stream_kernel(const StreamParams sp)
             ld_id = clamp_page(ld_bt[ld_pg], p.num_pages);                                        \
     } while (0)
 #define ADR_ISSUE(STAGE)                                                                          \
-    do { /* issue the cursor's page, or a group of null loads, into a ring stage */               \
-        char *tile_ = ring + (STAGE) * (2 * kTileBytes);                                          \
+    do { /* fill a ring stage with the cursor's page, or with a group of null loads */            \
+        const int stage_ = (STAGE);                                                               \
+        char *tile_ = ring + stage_ * kStageBytes;                                                \
         if (ld_ok) {                                                                              \
             issue_page(tile_, page_rsrc(kc, ld_id, page_bytes), page_rsrc(vc, ld_id, page_bytes), \
                        k_lane, v_lane, ld_head);                                                  \
+            real_mask |= 1 << stage_;                                                             \
             ld_pg += kWaves;                                                                      \
             ADR_SETTLE();                                                                         \
         } else {                                                                                  \
             issue_page(tile_, null_rsrc, null_rsrc, k_lane, v_lane, 0);                           \
+            real_mask &= ~(1 << stage_);                                                          \
         }                                                                                         \
     } while (0)
     ADR_SETTLE();
-    int stage = 0;
-    if (ld_ok && !ld_in_next)
-        ADR_ISSUE(stage); // first page of the first item
+    // Ring state: stages stage .. stage+S-2 (mod S) hold the next S-1 slots of the
+    // stream in order, stage-1 is free; real_mask marks the slots that hold a page.
+    int stage = 0, real_mask = 0;
+    for (int s0 = 0; s0 < S - 1; ++s0)
+        ADR_ISSUE(s0);
 
     uint32_t next_ticket = 0;
     // Drawn once per item, after the item's first page has been consumed (so that
@@ -344,47 +372,51 @@ void decode_stream_kernel(const StreamParams sp)
         for (int kk = 0; kk < 4; ++kk)
             qb[kk] = *(const u32x4 *)(sh.qtile[k & 1] + k_read[kk]);
 
-        const bool ran = C.pg < C.pg_end;
+        bool looked = false;
         for (int pg = C.pg; pg < C.pg_end; pg += kWaves) {
-            ADR_ISSUE(stage ^ 1);
-            wait_older_page();
-            const char *tile = ring + stage * (2 * kTileBytes);
+            // Step through the ring to the slot that holds this page: every step
+            // refills the stage freed by the step before; null slots are passed over.
+            for (;;) {
+                ADR_ISSUE(stage == 0 ? S - 1 : stage - 1);
+                if ((real_mask >> stage) & 1)
+                    break;
+                stage = stage + 1 == S ? 0 : stage + 1;
+            }
+            wait_ring(S);
+            const char *tile = ring + stage * kStageBytes;
             PageRegs pr;
 #pragma unroll
             for (int u = 0; u < 4; ++u)
                 pr.v[u] = *(const u32x4 *)(tile + kTileBytes + v_read + u * (D * 2));
             attend_page(st, pr, tile, k_read, qb, p.scale_log2e, pg * kPageSize + 4 * j, C.t1, j);
-            stage ^= 1;
-            if (pg == C.pg)
+            real_mask &= ~(1 << stage);
+            stage = stage + 1 == S ? 0 : stage + 1;
+            if (!looked) {
+                looked = true;
                 ADR_LOOK_AHEAD();
+            }
         }
-        if (!ran)
+        if (!looked)
             ADR_LOOK_AHEAD();
-        // `stage` now names the ring stage that receives the next item's first page:
-        // issued by the last iteration above, or here when this wave had no page.
-        if (!ran && ld_ok && ld_in_next)
-            ADR_ISSUE(stage);
 
-        // ---- combine the four waves; scratch = the stage not being filled
+        // ---- combine the four waves through the staging area of this item's parity
         float l = st.l;
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        const int scratch_off = wave * (kStages * 2 * kTileBytes) + (stage ^ 1) * (2 * kTileBytes);
-        // The scratch stage has no load in flight: every group that targeted it was
-        // waited for before its page was consumed.  Wave 0 needs the ticket it drew
-        // and the query tile it requested after the item's first page: at least one
-        // load group has been issued since if the wave had a second page, otherwise
-        // everything is waited for.
+        // Wave 0 needs the ticket it drew and the query tile it requested after the
+        // item's first page.  Each later page of the wave issued one more load
+        // group, so after S - 1 of them the ring's own wait count covers both;
+        // a shorter item waits for everything.
         if (wave == 0) {
-            if (C.pg + kWaves < C.pg_end)
-                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            if (C.pg + (S - 1) * kWaves < C.pg_end)
+                wait_ring(S);
             else
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
-        float *so = (float *)(lds_raw + scratch_off); // [G][D]
+        float *so = staging + ((k & 1) * kWaves + wave) * (G * D); // [G][D]
         if (j == 0 && r < G) {
-            sh.ml[wave][r][0] = st.m;
-            sh.ml[wave][r][1] = l;
+            sh.ml[k & 1][wave][r][0] = st.m;
+            sh.ml[k & 1][wave][r][1] = l;
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -394,24 +426,25 @@ void decode_stream_kernel(const StreamParams sp)
                 *(f32x4 *)(so + g * D + 8 * r + 4) = f32x4{st.o[4][i], st.o[5][i], st.o[6][i], st.o[7][i]};
             }
         }
-        if (lane == 0)
-            sh.stage_off[wave] = scratch_off;
         if (tid == 0)
             sh.slot[k & 1] = (int)next_ticket;
         ring_barrier();
+        // Nothing written above is written again before the barrier of the item after
+        // the next one, which no wave reaches before all have finished reading here.
 
+        const float *sbase = staging + (k & 1) * kWaves * (G * D);
         for (int idx = tid; idx < G * D; idx += kThreads) {
             const int g = idx / D, dd = idx - g * D;
-            float M = sh.ml[0][g][0];
+            float M = sh.ml[k & 1][0][g][0];
 #pragma unroll
             for (int w = 1; w < kWaves; ++w)
-                M = fmaxf(M, sh.ml[w][g][0]);
+                M = fmaxf(M, sh.ml[k & 1][w][g][0]);
             float acc = 0.f, den = 0.f;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) {
-                const float f = fast_exp2(sh.ml[w][g][0] - M);
-                acc += f * ((const float *)(lds_raw + sh.stage_off[w]))[g * D + dd];
-                den += f * sh.ml[w][g][1];
+                const float f = fast_exp2(sh.ml[k & 1][w][g][0] - M);
+                acc += f * sbase[w * (G * D) + g * D + dd];
+                den += f * sh.ml[k & 1][w][g][1];
             }
             const float o = den > 0.f ? acc / den : 0.f;
             const float lse = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
@@ -432,7 +465,6 @@ void decode_stream_kernel(const StreamParams sp)
             }
         }
         const int following = sh.slot[k & 1];
-        ring_barrier(); // scratch stages and the ticket slot are free again
 
         // ---- next item becomes current
         C = N;
@@ -485,23 +517,21 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, hipStream_t stream
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess || dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
-    const size_t lds = kRingBytes + sizeof(Shared);
+    // Ring depth by group size: what one workgroup's LDS holds next to the staging area.
+    const int stages = p.G <= 4 ? 4 : p.G <= 8 ? 3 : 2;
+    const size_t lds = (size_t)kWaves * stages * kStageBytes + sizeof(Shared) +
+                       (size_t)2 * kWaves * p.G * D * sizeof(float);
     if (!ready[dev].load(std::memory_order_acquire)) {
         DeviceInfo di;
         if ((e = hipGetSymbolAddress((void **)&di.tickets, HIP_SYMBOL(g_tickets))) != hipSuccess)
             return e;
         if ((e = hipFuncSetAttribute((const void *)decode_stream_kernel,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes)) != hipSuccess)
             return e;
-        int cus = 0, per_cu = 0;
+        int cus = 0;
         if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess)
             return e;
-        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel, kThreads,
-                                                              lds)) != hipSuccess)
-            return e;
-        if (per_cu < 1)
-            per_cu = 1;
-        di.workgroups = cus * per_cu;
+        di.workgroups = cus; // one workgroup per compute unit: each takes most of its LDS
         info[dev] = di;
         ready[dev].store(1, std::memory_order_release);
     }
@@ -509,6 +539,9 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, hipStream_t stream
     sp.d = p;
     sp.ticket = info[dev].tickets + 2 * (g_next_slot.fetch_add(1) % kTicketSlots);
     sp.pt = p.partition_tokens > 0 ? p.partition_tokens : (1 << 30);
+    sp.stages = stages;
+    if (lds > (size_t)kMaxLdsBytes)
+        return hipErrorInvalidValue;
     int64_t grid = (int64_t)p.B * p.Hkv * p.max_parts;
     if (grid > info[dev].workgroups)
         grid = info[dev].workgroups;

@@ -1,8 +1,10 @@
 // Log-sum-exp merge of per-partition attention results.
 //
 // One group of d/4 threads per (request, head) row; each thread owns four
-// consecutive output elements (16-byte loads of the fp32 partials).  Two sweeps
-// over the row's partitions: the largest lse, then the weighted sum.
+// consecutive output elements (16-byte loads of the fp32 partials).  One sweep
+// over the row's partitions, eight at a time with all their loads issued before
+// any is used, carrying a running maximum of the lse values (fixed order, so the
+// result is the same from run to run).
 #include "adr_device.h"
 
 namespace adr {
@@ -30,21 +32,39 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(const MergeParams p)
             return; // the attention kernel already wrote this row's final result
     }
 
-    float top = -INFINITY;
-    for (int i = 0; i < count; ++i)
-        top = fmaxf(top, p.part_lse[(int64_t)(first + i) * p.heads + h]);
-
+    constexpr int CH = 8;
+    float top = -INFINITY, total = 0.f;
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-    float total = 0.f;
-    if (top > -INFINITY) {
-        for (int i = 0; i < count; ++i) {
-            const int64_t pr = (int64_t)(first + i) * p.heads + h;
-            const float w = fast_exp2((p.part_lse[pr] - top) * kLog2e);
-            if (w > 0.f) { // an empty partition's payload is never touched
-                const f32x4 x = *(const f32x4 *)(p.part_o + pr * D + col);
-                acc += w * x;
-                total += w;
+    for (int i0 = 0; i0 < count; i0 += CH) {
+        float ls[CH];
+        f32x4 xs[CH];
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int64_t pr = (int64_t)(first + min(i0 + u, count - 1)) * p.heads + h;
+            ls[u] = p.part_lse[pr];
+            xs[u] = *(const f32x4 *)(p.part_o + pr * D + col);
+        }
+        float cm = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            if (i0 + u >= count)
+                ls[u] = -INFINITY; // the clamped re-reads of the last partition carry no mass
+            cm = fmaxf(cm, ls[u]);
+        }
+        const float nt = fmaxf(top, cm);
+        if (nt > -INFINITY) {
+            const float rs = fast_exp2((top - nt) * kLog2e); // 0 when nothing was seen before
+            acc *= rs;
+            total *= rs;
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                const float w = fast_exp2((ls[u] - nt) * kLog2e);
+                if (w > 0.f) { // an empty partition's payload is never used
+                    acc += w * xs[u];
+                    total += w;
+                }
             }
+            top = nt;
         }
     }
     const float inv = total > 0.f ? 1.f / total : 0.f;
