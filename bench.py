@@ -153,8 +153,13 @@ def main():
     merge_ms = np.array([e1.elapsed_time(e2) for _, e1, e2 in events])
     bytes_per_launch = kv_bytes / (layers * K)
     achieved = bytes_per_launch / (attn_ms.mean() * 1e-3) / 1e9
-    kernel_name = "decode_mfma_kernel" if (flags == adr.KERNEL_MFMA or (flags == adr.KERNEL_AUTO and wl.d == 128)) \
-        else "decode_valu_kernel"
+    G = wl.Hq // wl.Hkv
+    if flags == adr.KERNEL_VALU or wl.d != 128:
+        kernel_name = "decode_valu_kernel"
+    elif wl.B <= 512 and (flags == adr.KERNEL_MFMA or (part > 0 and st["max_len"] > part and G <= 4)):
+        kernel_name = "decode_stream_kernel"
+    else:
+        kernel_name = "decode_mfma_kernel"
     traffic = MEASURED_TRAFFIC_BYTES.get((wl.ident, kernel_name))
     roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,

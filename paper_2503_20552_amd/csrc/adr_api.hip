@@ -148,12 +148,23 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
         if (!adr::decode_mfma_supports(d, G))
             return ADR_ERR_UNSUPPORTED;
         kernel = MFMA_GRID;
-    } else if (want == ADR_KERNEL_MFMA || want == ADR_KERNEL_AUTO) {
+    } else if (want == ADR_KERNEL_MFMA) {
         if (adr::decode_stream_supports(d, G, B))
             kernel = MFMA_STREAM;
         else if (adr::decode_mfma_supports(d, G))
             kernel = MFMA_GRID;
-        else if (want == ADR_KERNEL_AUTO && adr::decode_valu_supports(d, G))
+        else
+            return ADR_ERR_UNSUPPORTED;
+    } else if (want == ADR_KERNEL_AUTO) {
+        // Measured on MI355X: the resident-workgroup kernel wins on split passes of
+        // small groups (many equal items); whole-row items and the wide-group shape
+        // run faster one workgroup per item.
+        const bool splits = partition_tokens > 0 && max_seq_len > partition_tokens;
+        if (splits && G <= 4 && adr::decode_stream_supports(d, G, B))
+            kernel = MFMA_STREAM;
+        else if (adr::decode_mfma_supports(d, G))
+            kernel = MFMA_GRID;
+        else if (adr::decode_valu_supports(d, G))
             kernel = VALU;
         else
             return ADR_ERR_UNSUPPORTED;

@@ -35,6 +35,14 @@
 
 namespace adr {
 
+__device__ __forceinline__ void read_k_operand(u32x4 (&ka)[4], const char *ktile,
+                                               const uint32_t (&k_read)[4])
+{
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        ka[kk] = *(const u32x4 *)(ktile + k_read[kk]);
+}
+
 __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParams p)
 {
     const int Hkv = p.Hkv, G = p.G;
@@ -107,6 +115,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
     int pg = t0 / kPageSize + wave;
     if (pg < pg_end) {
         PageRegs A, B;
+        u32x4 ka[4];
         const int last = pg + (pg_end - 1 - pg) / kWaves * kWaves; // this wave's last page
         int page = clamp_page(bt[pg], p.num_pages);
         int page_next = clamp_page(bt[min(pg + kWaves, last)], p.num_pages);
@@ -118,7 +127,8 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
             load_page(B, tile1, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes),
                       k_lane, v_lane, tok_bytes);
             wait_older_page();
-            attend_page(st, A, tile0, k_read, qb, p.scale_log2e, pg * kPageSize + 4 * j, t1, j);
+            read_k_operand(ka, tile0, k_read);
+            attend_page(st, A, ka, qb, p.scale_log2e, 1.f, pg * kPageSize + 4 * j, t1, j);
             pg += kWaves;
             if (pg >= pg_end)
                 break;
@@ -127,7 +137,8 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
             load_page(A, tile0, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes),
                       k_lane, v_lane, tok_bytes);
             wait_older_page();
-            attend_page(st, B, tile1, k_read, qb, p.scale_log2e, pg * kPageSize + 4 * j, t1, j);
+            read_k_operand(ka, tile1, k_read);
+            attend_page(st, B, ka, qb, p.scale_log2e, 1.f, pg * kPageSize + 4 * j, t1, j);
             pg += kWaves;
             if (pg >= pg_end)
                 break;

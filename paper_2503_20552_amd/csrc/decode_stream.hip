@@ -388,7 +388,11 @@ void decode_stream_kernel(const StreamParams sp)
 #pragma unroll
             for (int u = 0; u < 4; ++u)
                 pr.v[u] = *(const u32x4 *)(tile + kTileBytes + v_read + u * (D * 2));
-            attend_page(st, pr, tile, k_read, qb, p.scale_log2e, pg * kPageSize + 4 * j, C.t1, j);
+            u32x4 ka[4];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                ka[kk] = *(const u32x4 *)(tile + k_read[kk]);
+            attend_page(st, pr, ka, qb, p.scale_log2e, 1.f, pg * kPageSize + 4 * j, C.t1, j);
             real_mask &= ~(1 << stage);
             stage = stage + 1 == S ? 0 : stage + 1;
             if (!looked) {

@@ -61,15 +61,30 @@ struct WaveState {
     float l;    // this lane's share of head r's denominator
 };
 
-// One page: S = K Q^T, online softmax, O += P V.
-__device__ __forceinline__ void attend_page(WaveState &st, PageRegs &pg, const char *ktile,
-                                            const uint32_t (&k_read)[4], const u32x4 (&qb)[4],
-                                            float scale_log2e, int tok, int t1, int j)
+// Eight OCP E4M3 bytes -> eight bf16 (exact: three mantissa bits fit in seven).
+// The hardware conversion gives fp32 pairs; their upper halves are the bf16 values.
+__device__ __forceinline__ u32x4 fp8x8_to_bf16x8(u32x2 w)
 {
-    u32x4 ka[4];
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    u32x4 r;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-        ka[kk] = *(const u32x4 *)(ktile + k_read[kk]);
+    for (int h = 0; h < 2; ++h) {
+        const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[h], false);
+        const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[h], true);
+        r[2 * h] = __builtin_amdgcn_perm(__float_as_uint(lo[1]), __float_as_uint(lo[0]), 0x07060302u);
+        r[2 * h + 1] = __builtin_amdgcn_perm(__float_as_uint(hi[1]), __float_as_uint(hi[0]), 0x07060302u);
+    }
+    return r;
+}
+
+// One page: S = K Q^T, online softmax, O += P V.
+//   ka           A operand of QK^T (see decode_mfma.hip), one register group per step
+//   score_scale  softmax scale * log2(e) (* the page's K scale for an fp8 cache)
+//   p_scale      1, or the page's V scale for an fp8 cache: O += (P * p_scale) V
+__device__ __forceinline__ void attend_page(WaveState &st, PageRegs &pg, const u32x4 (&ka)[4],
+                                            const u32x4 (&qb)[4], float score_scale, float p_scale,
+                                            int tok, int t1, int j)
+{
     f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
@@ -80,7 +95,7 @@ __device__ __forceinline__ void attend_page(WaveState &st, PageRegs &pg, const c
     float sc[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        sc[i] = s[i] * scale_log2e;
+        sc[i] = s[i] * score_scale;
         if (tail && tok + i >= t1)
             sc[i] = -INFINITY;
     }
@@ -111,8 +126,9 @@ __device__ __forceinline__ void attend_page(WaveState &st, PageRegs &pg, const c
     uint32_t ph[4], pl[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const float pw = fast_exp2(sc[i] - st.m);
+        float pw = fast_exp2(sc[i] - st.m);
         st.l += pw;
+        pw *= p_scale;
         ph[i] = __float_as_uint(pw) & 0xffff0000u;            // bf16 head (truncated)
         pl[i] = __float_as_uint(pw - __uint_as_float(ph[i])); // remainder, exact in fp32
     }
