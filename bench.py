@@ -33,7 +33,10 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of this command (see profiles/), scaled by the same counters'
 # reading on adr_probe_copy.  None until such a run has been recorded.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    (3, "decode_stream_kernel"): 2342303642,   # profiles/decode_stream_kernel_workload3.md
+    (3, "decode_mfma_kernel"): 2338000000,     # profiles/decode_mfma_kernel_workload3.md
+}
 
 
 def log(msg):
