@@ -43,15 +43,26 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def build_state(wl: W.Workload, layers: int, total_steps: int):
+def build_state(wl: W.Workload, layers: int, total_steps: int, fp8: bool = False):
     dev = "cuda:0"
     b = W.make_batch(wl, device=dev, headroom_tokens=total_steps + 1)
-    caches = [adr.KVCache(b.k_cache, b.v_cache)]
+
+    def as_cache(k, v):
+        if not fp8:
+            return adr.KVCache(k, v)
+        k8, ks = W.quantize_pool_fp8(k, b.used)      # host-style quantiser (library casts), on the device
+        v8, vs = W.quantize_pool_fp8(v, b.used)
+        return adr.KVCache(k8, v8, ks, vs)
+
+    caches = [as_cache(b.k_cache, b.v_cache)]
     for i in range(1, layers):
         used = b.used
-        caches.append(adr.KVCache(
+        caches.append(as_cache(
             W.fill_pool_bf16(b.num_pages, wl.page_size, wl.Hkv, wl.d, used, wl.seed + 100 + 2 * i, dev),
             W.fill_pool_bf16(b.num_pages, wl.page_size, wl.Hkv, wl.d, used, wl.seed + 101 + 2 * i, dev)))
+    if fp8:
+        b.k_cache = b.v_cache = None                 # the bf16 originals are not needed any more
+        torch.cuda.empty_cache()
     # one grouped q|k|v buffer per step, as the executor receives it
     width = (wl.Hq + 2 * wl.Hkv) * wl.d
     qkv = W.randn_bf16((wl.B, width), wl.seed + 7, dev)
@@ -76,6 +87,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="resident layer caches (0 = the workload's)")
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--partition", type=int, default=-1, help="partition tokens (-1 = the workload's)")
+    ap.add_argument("--cache-dtype", default="bf16", choices=["bf16", "fp8"],
+                    help="fp8: caches quantised to e4m3 bytes with one fp32 scale per (page, kv-head)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch adr_probe_copy once on 1 GiB (calibrates profiler byte counters)")
@@ -97,17 +110,20 @@ def main():
     total_steps = K + Wm
 
     t0 = time.time()
-    st = build_state(wl, layers, total_steps)
+    fp8 = args.cache_dtype == "fp8"
+    st = build_state(wl, layers, total_steps, fp8)
     b = st["batch"]
+    elem = 1 if fp8 else 2
     torch.cuda.synchronize()
     log("workload %d %s: B=%d Hq=%d Hkv=%d d=%d layers=%d partition=%d pool=%d pages (%.1f GB K+V resident) "
         "lengths %s; set-up %.1f s" % (wl.ident, wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, layers, part, b.num_pages,
-                                      layers * 2 * b.k_cache.numel() * 2 / 1e9, W.describe_lengths(b.seq_lens),
+                                      layers * 2 * st["caches"][0].k.numel() * elem / 1e9, W.describe_lengths(b.seq_lens),
                                       time.time() - t0))
     out = torch.empty((wl.B, wl.Hq, wl.d), dtype=torch.bfloat16, device="cuda:0")
     ws_bytes = adr.adr_decode_workspace_bytes(wl.B, wl.Hq, wl.d, st["max_len"], part)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda:0")
-    bytes_per_token = 2 * wl.Hkv * wl.d * 2          # K and V, bf16, one layer
+    # K and V of one token in one layer (+ an fp8 page's two scales per kv-head, shared by its 16 tokens)
+    bytes_per_token = 2 * wl.Hkv * wl.d * elem + (2 * wl.Hkv * 4 / wl.page_size if fp8 else 0)
 
     def one_step(s, events=None):
         pos, seq = st["positions"][s], st["seq_lens"][s]
@@ -157,13 +173,13 @@ def main():
     bytes_per_launch = kv_bytes / (layers * K)
     achieved = bytes_per_launch / (attn_ms.mean() * 1e-3) / 1e9
     G = wl.Hq // wl.Hkv
-    if flags == adr.KERNEL_VALU or wl.d != 128:
+    if flags == adr.KERNEL_VALU or wl.d != 128 or (fp8 and wl.B > 512):
         kernel_name = "decode_valu_kernel"
-    elif wl.B <= 512 and (flags == adr.KERNEL_MFMA or (part > 0 and st["max_len"] > part and G <= 4)):
+    elif wl.B <= 512 and (fp8 or flags == adr.KERNEL_MFMA or (part > 0 and st["max_len"] > part and G <= 4)):
         kernel_name = "decode_stream_kernel"
     else:
         kernel_name = "decode_mfma_kernel"
-    traffic = MEASURED_TRAFFIC_BYTES.get((wl.ident, kernel_name))
+    traffic = MEASURED_TRAFFIC_BYTES.get((wl.ident, kernel_name)) if not fp8 else None
     roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "avg_kernel_ms": round(float(attn_ms.mean()), 5), "launches": int(len(attn_ms)),
@@ -174,17 +190,19 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(wl, st, Wm)
+        cpu = cpu_baseline(wl, st, Wm, bytes_per_token)
 
     line = {
         "metric": "decode_attention_attended_kv_bandwidth",
         "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(elapsed / K * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d page=16 bf16, %d resident layers, partition %d + LSE merge, "
-                               "lengths %s" % (wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, layers, part, wl.lengths),
-                   "kernel": args.kernel, "layers": layers, "partition_tokens": part},
+        "dtype": args.cache_dtype, "data": "synthetic",
+        "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d page=16 %s cache, %d resident layers, partition %d + LSE "
+                               "merge, lengths %s" % (wl.name, wl.B, wl.Hq, wl.Hkv, wl.d,
+                                                      "fp8-e4m3" if fp8 else "bf16", layers, part, wl.lengths),
+                   "kernel": args.kernel, "layers": layers, "partition_tokens": part,
+                   "cache_dtype": args.cache_dtype},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
         "attended_tokens_per_s": round(attended_tokens / elapsed, 1),
         "roofline": roofline,
@@ -194,7 +212,7 @@ def main():
     return 0
 
 
-def cpu_baseline(wl, st, step):
+def cpu_baseline(wl, st, step, bytes_per_token):
     """The fp64 oracle, untuned, on this machine's host cores over a bounded sample:
     whole layers of the same workload at the first timed step's lengths, as many
     as give roughly 10-30 s of CPU work."""
@@ -208,12 +226,15 @@ def cpu_baseline(wl, st, step):
     for li in range(n_layers):
         cache = st["caches"][li]
         kh, vh = W.bits(cache.k), W.bits(cache.v)           # device -> host copy, not timed
+        scales = {}
+        if cache.k_scale is not None:
+            scales = dict(k_scale=W.bits(cache.k_scale), v_scale=W.bits(cache.v_scale))
         t0 = time.perf_counter()
-        _, _, threads = oracle.decode_attention(qh, kh, vh, b.block_table, seq, wl.scale)
+        _, _, threads = oracle.decode_attention(qh, kh, vh, b.block_table, seq, wl.scale, **scales)
         dt += time.perf_counter() - t0
         del kh, vh
     tokens = int(seq.sum()) * n_layers
-    gbs = tokens * 2 * wl.Hkv * wl.d * 2 / dt / 1e9
+    gbs = tokens * bytes_per_token / dt / 1e9
     log("cpu oracle: %d layer(s), %d attended tokens, %.2f s on %d threads -> %.3f GB/s" % (
         n_layers, tokens, dt, threads, gbs))
     return {"value": round(gbs, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",

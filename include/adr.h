@@ -53,10 +53,11 @@ typedef enum { ADR_BF16 = 0, ADR_FP8_E4M3 = 1, ADR_F32 = 2 } adr_dtype;
 enum {
     ADR_KERNEL_AUTO = 0, /* the library picks per shape */
     ADR_KERNEL_VALU = 1, /* vector-ALU dot products, any supported shape */
-    ADR_KERNEL_MFMA = 2, /* matrix-core QK^T and PV (d = 128, bf16 cache): resident workgroups
-                            pulling (request, partition, kv-head) items when B <= 1024, else
-                            the one-workgroup-per-item form below */
-    ADR_KERNEL_MFMA_GRID = 3, /* matrix cores, one workgroup per (request, partition, kv-head) */
+    ADR_KERNEL_MFMA = 2, /* matrix-core QK^T and PV (d = 128): resident workgroups pulling
+                            (request, partition, kv-head) items when B <= 512, else (bf16
+                            cache only) the one-workgroup-per-item form below */
+    ADR_KERNEL_MFMA_GRID = 3, /* matrix cores, one workgroup per (request, partition, kv-head);
+                                 bf16 cache only */
     /* Bit 4: run the partition pass only and leave the merge to a later
      * adr_decode_merge call on the same workspace (rows with one partition are
      * still written to `out` directly).  Lets a caller place the two passes on

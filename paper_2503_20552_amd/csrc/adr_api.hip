@@ -5,9 +5,9 @@
 
 namespace adr {
 hipError_t launch_kv_append(const AppendParams &p, bool fp8, hipStream_t stream);
-hipError_t launch_decode_valu(const DecodeParams &p, int d, hipStream_t stream);
+hipError_t launch_decode_valu(const DecodeParams &p, int d, bool fp8, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeParams &p, int d, hipStream_t stream);
-hipError_t launch_decode_stream(const DecodeParams &p, int d, hipStream_t stream);
+hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStream_t stream);
 bool decode_stream_supports(int d, int G, int B);
 bool decode_valu_supports(int d, int G);
 bool decode_mfma_supports(int d, int G);
@@ -137,21 +137,19 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
     const int d = cache->d;
     const unsigned want = flags & 0xFu;
     const bool fp8 = cache->dtype == ADR_FP8_E4M3;
-    if (fp8)
-        return ADR_ERR_UNSUPPORTED; // fp8 caches can be appended to but not attended yet
     enum { VALU, MFMA_GRID, MFMA_STREAM } kernel;
     if (want == ADR_KERNEL_VALU) {
         if (!adr::decode_valu_supports(d, G))
             return ADR_ERR_UNSUPPORTED;
         kernel = VALU;
     } else if (want == ADR_KERNEL_MFMA_GRID) {
-        if (!adr::decode_mfma_supports(d, G))
+        if (fp8 || !adr::decode_mfma_supports(d, G))
             return ADR_ERR_UNSUPPORTED;
         kernel = MFMA_GRID;
     } else if (want == ADR_KERNEL_MFMA) {
         if (adr::decode_stream_supports(d, G, B))
             kernel = MFMA_STREAM;
-        else if (adr::decode_mfma_supports(d, G))
+        else if (!fp8 && adr::decode_mfma_supports(d, G))
             kernel = MFMA_GRID;
         else
             return ADR_ERR_UNSUPPORTED;
@@ -160,9 +158,10 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
         // small groups (many equal items); whole-row items and the wide-group shape
         // run faster one workgroup per item.
         const bool splits = partition_tokens > 0 && max_seq_len > partition_tokens;
-        if (splits && G <= 4 && adr::decode_stream_supports(d, G, B))
+        // An fp8 cache has the resident-workgroup kernel and the vector-ALU one only.
+        if ((fp8 || (splits && G <= 4)) && adr::decode_stream_supports(d, G, B))
             kernel = MFMA_STREAM;
-        else if (adr::decode_mfma_supports(d, G))
+        else if (!fp8 && adr::decode_mfma_supports(d, G))
             kernel = MFMA_GRID;
         else if (adr::decode_valu_supports(d, G))
             kernel = VALU;
@@ -215,9 +214,9 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
     p.out_f32 = out_dtype == ADR_F32;
     p.scale_log2e = scale * adr::kLog2e;
 
-    hipError_t e = kernel == MFMA_STREAM ? adr::launch_decode_stream(p, d, (hipStream_t)stream)
+    hipError_t e = kernel == MFMA_STREAM ? adr::launch_decode_stream(p, d, fp8, (hipStream_t)stream)
                    : kernel == MFMA_GRID ? adr::launch_decode_mfma(p, d, (hipStream_t)stream)
-                                         : adr::launch_decode_valu(p, d, (hipStream_t)stream);
+                                         : adr::launch_decode_valu(p, d, fp8, (hipStream_t)stream);
     if (e != hipSuccess)
         return ADR_ERR_LAUNCH;
     if (split && !(flags & ADR_PARTIALS_ONLY)) {

@@ -1,4 +1,5 @@
-// Persistent matrix-core decode attention (d = 128, bf16 cache, G <= 16, B <= 512).
+// Persistent matrix-core decode attention (d = 128, bf16 or fp8-e4m3 cache, G <= 16,
+// B <= 512).
 //
 // The grid is a fixed number of workgroups (a couple per compute unit) that
 // stay resident and pull work items from a ticket counter until none is left.
@@ -31,18 +32,37 @@
 //  * The cross-wave combination of an item goes through a double-buffered
 //    staging area, so one barrier per item is enough.
 //
+// fp8 cache: a page of one kv-head is half the bytes (two loads per tile instead
+// of four), and two more 4-byte direct-to-LDS loads bring the page's K and V
+// scales into the tail of the ring stage.  The bytes are widened to bf16 (exact)
+// after the LDS read and enter the same matrix instructions; the K scale is
+// folded into the score scale and the V scale into the weights.  The ring is
+// deeper, since a stage is smaller.
+//
 // The ticket counter and a finished-workgroups counter live in a small pool of
 // static device words that are zero whenever no launch is using them: the last
 // workgroup to finish puts both back to zero.
 #include "mfma_page.h"
 
+#include <algorithm>
 #include <atomic>
 
 namespace adr {
 
 constexpr int kMaxStreamB = 512;
 constexpr int kTicketSlots = 64;
-constexpr int kStageBytes = 2 * kTileBytes; // one ring stage: K tile, then V tile
+
+// Geometry of one ring stage: K tile, V tile, then (fp8) the two scales, each
+// in a 256-byte slot of its own (a 4-byte direct-to-LDS load covers 64 x 4 bytes).
+template <bool FP8> struct Geo {
+    static constexpr int kRow = FP8 ? D : 2 * D;          // bytes of one token of one kv-head
+    static constexpr int kTile = kPageSize * kRow;        // 2 KB / 4 KB
+    static constexpr int kTileLoads = kTile / 1024;       // 16-byte-per-lane loads per tile
+    static constexpr int kScaleSlot = 256;
+    static constexpr int kStage = 2 * kTile + (FP8 ? 2 * kScaleSlot : 0);
+    static constexpr int kGroup = 2 * kTileLoads + (FP8 ? 2 : 0); // loads per page
+    static constexpr int kMaxStages = FP8 ? 6 : 4;
+};
 
 __device__ uint32_t g_tickets[kTicketSlots][2];
 
@@ -50,7 +70,7 @@ struct StreamParams {
     DecodeParams d;
     uint32_t *ticket; // {next ticket, workgroups finished}
     int pt;           // tokens per partition (2^30 when the pass is not split)
-    int stages;       // ring stages per wave (2..4)
+    int stages;       // ring stages per wave (2 .. Geo::kMaxStages)
 };
 
 struct Item {
@@ -67,7 +87,7 @@ typedef const __attribute__((address_space(4))) int32_t *table_ptr;
 constexpr int kMaxLdsBytes = 160 * 1024;  // LDS of one compute unit
 constexpr int kQTileBytes = 16 * D * 2; // sixteen query rows (heads of a group, zero beyond G)
 
-// LDS layout: the ring (kWaves * stages * kStageBytes), this block, then the
+// LDS layout: the ring (kWaves * stages * Geo::kStage), this block, then the
 // staging area float[2][kWaves][G][D] for the per-wave results of an item.
 struct Shared {
     char qtile[2][kQTileBytes]; // query tile of the current / the next item, rows swizzled like K
@@ -152,23 +172,36 @@ __device__ __forceinline__ void issue_query(char *qtile, const StreamParams &sp,
     asm volatile("" ::: "memory");
 }
 
-// Eight direct-to-LDS loads: K rows (swizzled) then V rows (natural) of one page
-// for one kv-head into ring stage `tile` (K tile, then V tile).
+// The direct-to-LDS loads of one page for one kv-head into ring stage `tile`:
+// K rows (swizzled), V rows (natural) and, for an fp8 cache, the page's two
+// scales (lane 0 only: the other lanes' offsets are out of the descriptor's range).
+template <bool FP8>
 __device__ __forceinline__ void issue_page(char *tile, __amdgpu_buffer_rsrc_t krsrc,
-                                           __amdgpu_buffer_rsrc_t vrsrc, const uint32_t (&k_lane)[4],
-                                           const uint32_t (&v_lane)[4], uint32_t head_bytes)
+                                           __amdgpu_buffer_rsrc_t vrsrc, __amdgpu_buffer_rsrc_t ksrsrc,
+                                           __amdgpu_buffer_rsrc_t vsrsrc, const uint32_t (&k_lane)[4],
+                                           const uint32_t (&v_lane)[4], uint32_t s_lane,
+                                           uint32_t head_bytes, uint32_t scale_bytes)
 {
+    typedef Geo<FP8> geo;
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < geo::kTileLoads; ++i)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             krsrc, (__attribute__((address_space(3))) void *)(tile + i * 1024), 16, k_lane[i],
             head_bytes, 0, 0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < geo::kTileLoads; ++i)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            vrsrc, (__attribute__((address_space(3))) void *)(tile + kTileBytes + i * 1024), 16,
+            vrsrc, (__attribute__((address_space(3))) void *)(tile + geo::kTile + i * 1024), 16,
             v_lane[i], head_bytes, 0, 0);
+    if (FP8) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            ksrsrc, (__attribute__((address_space(3))) void *)(tile + 2 * geo::kTile), 4, s_lane,
+            scale_bytes, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            vsrsrc, (__attribute__((address_space(3))) void *)(tile + 2 * geo::kTile + geo::kScaleSlot),
+            4, s_lane, scale_bytes, 0, 0);
+    }
     asm volatile("" ::: "memory");
 }
 
@@ -181,21 +214,32 @@ __device__ __forceinline__ void ring_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// Wait until all but the newest S - 1 load groups (of eight loads) have landed.
+// Wait until all but the newest S - 1 load groups have landed.
+template <bool FP8>
 __device__ __forceinline__ void wait_ring(int stages)
 {
-    if (stages == 4)
-        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-    else if (stages == 3)
-        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+#define ADR_WAIT_CASE(S)                                                                          \
+    case S:                                                                                       \
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 1) * Geo<FP8>::kGroup) : "memory");          \
+        break;
+    switch (stages) {
+        ADR_WAIT_CASE(6)
+        ADR_WAIT_CASE(5)
+        ADR_WAIT_CASE(4)
+        ADR_WAIT_CASE(3)
+    default:
+        ADR_WAIT_CASE(2)
+    }
+#undef ADR_WAIT_CASE
 }
 
+template <bool FP8>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 2)))
 void decode_stream_kernel(const StreamParams sp)
 {
     const DecodeParams &p = sp.d;
+    typedef Geo<FP8> geo;
+    constexpr int kStageBytes = geo::kStage;
     const int S = sp.stages;
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     const int ring_bytes = kWaves * S * kStageBytes;
@@ -273,23 +317,43 @@ void decode_stream_kernel(const StreamParams sp)
     }
 
     // ---- per-lane constants
-    const uint32_t tok_bytes = (uint32_t)Hkv * D * 2;
+    // bf16: a row is sixteen 16-byte chunks and a load covers four rows; slot c of row t
+    //       holds chunk c ^ t.  Step kk of QK^T reads chunk kk*4 + j of row r (8 elements).
+    // fp8:  a row is eight 16-byte chunks and a load covers eight rows; slot c of row t
+    //       holds chunk c ^ (t & 7).  The same 8 elements are the 8-byte piece kk*4 + j.
+    const uint32_t tok_bytes = (uint32_t)Hkv * geo::kRow;
     const uint32_t page_bytes = kPageSize * tok_bytes;
-    uint32_t k_lane[4], v_lane[4], q_lane[4], k_read[4];
+    uint32_t k_lane[4], v_lane[4], q_lane[4], k_read[4], q_read[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int t = 4 * i + j;                       // row this lane fetches in load i
-        k_lane[i] = t * tok_bytes + ((r ^ t) * 16);     // slot r of row t holds chunk r ^ t
-        v_lane[i] = t * tok_bytes + r * 16;
+        const int t = 4 * i + j; // query-tile row this lane fetches in load i
         q_lane[i] = t * (D * 2) + ((r ^ t) * 16);
-        k_read[i] = r * (D * 2) + (((i * 4 + j) ^ r) * 16);
+        q_read[i] = r * (D * 2) + (((i * 4 + j) ^ r) * 16);
+        if (FP8) {
+            const int tf = 8 * (i & 1) + (lane >> 3), c = lane & 7; // row / slot of load i (i < 2)
+            k_lane[i] = tf * tok_bytes + ((c ^ (tf & 7)) * 16);
+            v_lane[i] = tf * tok_bytes + c * 16;
+            const int piece = i * 4 + j;
+            k_read[i] = r * D + (((piece >> 1) ^ (r & 7)) * 16) + (piece & 1) * 8;
+        } else {
+            k_lane[i] = t * tok_bytes + ((r ^ t) * 16);
+            v_lane[i] = t * tok_bytes + r * 16;
+            k_read[i] = q_read[i];
+        }
     }
-    const uint32_t v_read = (4 * j) * (D * 2) + r * 16; // row 4j (+u), chunk r
+    // V operand: rows 4j + u, the 8 elements 8r .. 8r+7
+    const uint32_t v_read = (4 * j) * geo::kRow + r * (geo::kRow / 16);
+    const uint32_t s_lane = lane == 0 ? 0u : 0x7ffffff0u; // scale loads: only lane 0 is in range
     const char *kc = (const char *)p.k_cache;
     const char *vc = (const char *)p.v_cache;
     char *ring = lds_raw + wave * (S * kStageBytes);
     const __amdgpu_buffer_rsrc_t null_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)kc, 0, 0, 0x00020000); // every read is out of range: zeros
+    const int scale_range = FP8 ? p.num_pages * Hkv * 4 : 0;
+    const __amdgpu_buffer_rsrc_t ks_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(FP8 ? (const void *)p.k_scale : (const void *)kc), 0, scale_range, 0x00020000);
+    const __amdgpu_buffer_rsrc_t vs_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(FP8 ? (const void *)p.v_scale : (const void *)kc), 0, scale_range, 0x00020000);
 
     Item C = decode_ticket(sh, sp, sh.slot[0], wave);
     Item N = decode_ticket(sh, sp, sh.slot[1], wave);
@@ -304,7 +368,8 @@ void decode_stream_kernel(const StreamParams sp)
     // its own copy of what it needs from the item it is in.
     int ld_in_next = 0;
     int ld_pg = C.pg, ld_end = C.valid ? C.pg_end : 0;
-    uint32_t ld_head = (uint32_t)C.kvh * (D * 2);
+    uint32_t ld_head = (uint32_t)C.kvh * geo::kRow;
+    int ld_kvh = C.kvh;
     table_ptr ld_bt = (table_ptr)(p.block_table + (int64_t)C.b * p.max_pages);
     int ld_ok = 0, ld_id = 0;
 #define ADR_SETTLE()                                                                              \
@@ -313,7 +378,8 @@ void decode_stream_kernel(const StreamParams sp)
             ld_in_next = 1;                                                                       \
             ld_pg = N.pg;                                                                         \
             ld_end = N.valid ? N.pg_end : 0;                                                      \
-            ld_head = (uint32_t)N.kvh * (D * 2);                                                  \
+            ld_head = (uint32_t)N.kvh * geo::kRow;                                                \
+            ld_kvh = N.kvh;                                                                       \
             ld_bt = (table_ptr)(p.block_table + (int64_t)N.b * p.max_pages);                      \
         }                                                                                         \
         ld_ok = ld_pg < ld_end;                                                                   \
@@ -325,13 +391,15 @@ void decode_stream_kernel(const StreamParams sp)
         const int stage_ = (STAGE);                                                               \
         char *tile_ = ring + stage_ * kStageBytes;                                                \
         if (ld_ok) {                                                                              \
-            issue_page(tile_, page_rsrc(kc, ld_id, page_bytes), page_rsrc(vc, ld_id, page_bytes), \
-                       k_lane, v_lane, ld_head);                                                  \
+            issue_page<FP8>(tile_, page_rsrc(kc, ld_id, page_bytes),                              \
+                            page_rsrc(vc, ld_id, page_bytes), ks_rsrc, vs_rsrc, k_lane, v_lane,   \
+                            s_lane, ld_head, (uint32_t)(ld_id * Hkv + ld_kvh) * 4u);              \
             real_mask |= 1 << stage_;                                                             \
             ld_pg += kWaves;                                                                      \
             ADR_SETTLE();                                                                         \
         } else {                                                                                  \
-            issue_page(tile_, null_rsrc, null_rsrc, k_lane, v_lane, 0);                           \
+            issue_page<FP8>(tile_, null_rsrc, null_rsrc, null_rsrc, null_rsrc, k_lane, v_lane,    \
+                            s_lane, 0, 0);                                                        \
             real_mask &= ~(1 << stage_);                                                          \
         }                                                                                         \
     } while (0)
@@ -370,7 +438,7 @@ void decode_stream_kernel(const StreamParams sp)
         u32x4 qb[4]; // B operand of QK^T: head r's query, chunk order matching the K reads
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-            qb[kk] = *(const u32x4 *)(sh.qtile[k & 1] + k_read[kk]);
+            qb[kk] = *(const u32x4 *)(sh.qtile[k & 1] + q_read[kk]);
 
         bool looked = false;
         for (int pg = C.pg; pg < C.pg_end; pg += kWaves) {
@@ -382,17 +450,36 @@ void decode_stream_kernel(const StreamParams sp)
                     break;
                 stage = stage + 1 == S ? 0 : stage + 1;
             }
-            wait_ring(S);
+            wait_ring<FP8>(S);
             const char *tile = ring + stage * kStageBytes;
             PageRegs pr;
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                pr.v[u] = *(const u32x4 *)(tile + kTileBytes + v_read + u * (D * 2));
             u32x4 ka[4];
+            float score_scale = p.scale_log2e, p_scale = 1.f;
+            if (FP8) {
+                u32x2 vraw[4], kraw[4];
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                ka[kk] = *(const u32x4 *)(tile + k_read[kk]);
-            attend_page(st, pr, ka, qb, p.scale_log2e, 1.f, pg * kPageSize + 4 * j, C.t1, j);
+                for (int u = 0; u < 4; ++u)
+                    vraw[u] = *(const u32x2 *)(tile + geo::kTile + v_read + u * geo::kRow);
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    kraw[kk] = *(const u32x2 *)(tile + k_read[kk]);
+                score_scale *= *(const float *)(tile + 2 * geo::kTile);
+                p_scale = *(const float *)(tile + 2 * geo::kTile + geo::kScaleSlot);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    pr.v[u] = fp8x8_to_bf16x8(vraw[u]);
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    ka[kk] = fp8x8_to_bf16x8(kraw[kk]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    pr.v[u] = *(const u32x4 *)(tile + geo::kTile + v_read + u * geo::kRow);
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    ka[kk] = *(const u32x4 *)(tile + k_read[kk]);
+            }
+            attend_page(st, pr, ka, qb, score_scale, p_scale, pg * kPageSize + 4 * j, C.t1, j);
             real_mask &= ~(1 << stage);
             stage = stage + 1 == S ? 0 : stage + 1;
             if (!looked) {
@@ -413,7 +500,7 @@ void decode_stream_kernel(const StreamParams sp)
         // a shorter item waits for everything.
         if (wave == 0) {
             if (C.pg + (S - 1) * kWaves < C.pg_end)
-                wait_ring(S);
+                wait_ring<FP8>(S);
             else
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
@@ -506,7 +593,7 @@ bool decode_stream_supports(int d, int G, int B)
     return kStreamKernelEnabled && d == D && G >= 1 && G <= 16 && B <= kMaxStreamB;
 }
 
-hipError_t launch_decode_stream(const DecodeParams &p, int d, hipStream_t stream)
+hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStream_t stream)
 {
     if (!decode_stream_supports(d, p.G, p.B))
         return hipErrorInvalidValue;
@@ -521,15 +608,22 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, hipStream_t stream
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess || dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
-    // Ring depth by group size: what one workgroup's LDS holds next to the staging area.
-    const int stages = p.G <= 4 ? 4 : p.G <= 8 ? 3 : 2;
-    const size_t lds = (size_t)kWaves * stages * kStageBytes + sizeof(Shared) +
-                       (size_t)2 * kWaves * p.G * D * sizeof(float);
+    // Ring depth: what one workgroup's LDS holds next to the staging area of the group size.
+    const size_t fixed = sizeof(Shared) + (size_t)2 * kWaves * p.G * D * sizeof(float);
+    const int stage_bytes = fp8 ? Geo<true>::kStage : Geo<false>::kStage;
+    int stages = (int)(((size_t)kMaxLdsBytes - fixed) / ((size_t)kWaves * stage_bytes));
+    stages = std::min(stages, fp8 ? Geo<true>::kMaxStages : Geo<false>::kMaxStages);
+    if (stages < 2)
+        return hipErrorInvalidValue;
+    const size_t lds = (size_t)kWaves * stages * stage_bytes + fixed;
     if (!ready[dev].load(std::memory_order_acquire)) {
         DeviceInfo di;
         if ((e = hipGetSymbolAddress((void **)&di.tickets, HIP_SYMBOL(g_tickets))) != hipSuccess)
             return e;
-        if ((e = hipFuncSetAttribute((const void *)decode_stream_kernel,
+        if ((e = hipFuncSetAttribute((const void *)decode_stream_kernel<false>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes)) != hipSuccess)
+            return e;
+        if ((e = hipFuncSetAttribute((const void *)decode_stream_kernel<true>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes)) != hipSuccess)
             return e;
         int cus = 0;
@@ -544,12 +638,13 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, hipStream_t stream
     sp.ticket = info[dev].tickets + 2 * (g_next_slot.fetch_add(1) % kTicketSlots);
     sp.pt = p.partition_tokens > 0 ? p.partition_tokens : (1 << 30);
     sp.stages = stages;
-    if (lds > (size_t)kMaxLdsBytes)
-        return hipErrorInvalidValue;
     int64_t grid = (int64_t)p.B * p.Hkv * p.max_parts;
     if (grid > info[dev].workgroups)
         grid = info[dev].workgroups;
-    decode_stream_kernel<<<dim3((unsigned)grid), kThreads, lds, stream>>>(sp);
+    if (fp8)
+        decode_stream_kernel<true><<<dim3((unsigned)grid), kThreads, lds, stream>>>(sp);
+    else
+        decode_stream_kernel<false><<<dim3((unsigned)grid), kThreads, lds, stream>>>(sp);
     return hipGetLastError();
 }
 

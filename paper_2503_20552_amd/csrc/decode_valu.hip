@@ -1,4 +1,5 @@
-// Decode attention with vector-ALU dot products (any supported shape).
+// Decode attention with vector-ALU dot products (any supported shape, bf16 or
+// fp8-e4m3 cache).
 //
 // One workgroup of 4 waves per (request, kv-head, partition).  Wave w streams
 // pages w, w+4, ... of the partition.  A cache row (one token, one kv-head) is
@@ -8,11 +9,49 @@
 // same K/V registers.  Each (wave, token slot) keeps its own online-softmax
 // state (running max, denominator, weighted V sum), merged once at the end:
 // slots by wave shuffles, waves through LDS.
+//
+// An fp8 cache keeps the same lane <-> element mapping: a lane's eight elements
+// are 8 bytes, widened by the hardware converter; the page's K scale multiplies
+// the scores and its V scale the weights that enter the V sum.
 #include "adr_device.h"
 
 namespace adr {
 
-template <int D, int G>
+// Eight cache elements of one lane as fp32.
+template <bool FP8> struct Row8;
+template <> struct Row8<false> {
+    u32x4 w;
+    __device__ __forceinline__ void load(const void *cache, int64_t elem) { w = *(const u32x4 *)((const uint16_t *)cache + elem); }
+    __device__ __forceinline__ void clear() { w = u32x4{0u, 0u, 0u, 0u}; }
+    __device__ __forceinline__ void widen(float (&f)[8]) const
+    {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            f[2 * e] = bf16_lo(w[e]);
+            f[2 * e + 1] = bf16_hi(w[e]);
+        }
+    }
+};
+template <> struct Row8<true> {
+    u32x2 w;
+    __device__ __forceinline__ void load(const void *cache, int64_t elem) { w = *(const u32x2 *)((const uint8_t *)cache + elem); }
+    __device__ __forceinline__ void clear() { w = u32x2{0u, 0u}; }
+    __device__ __forceinline__ void widen(float (&f)[8]) const
+    {
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[h], false);
+            const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[h], true);
+            f[4 * h] = lo[0];
+            f[4 * h + 1] = lo[1];
+            f[4 * h + 2] = hi[0];
+            f[4 * h + 3] = hi[1];
+        }
+    }
+};
+
+template <int D, int G, bool FP8>
 __global__ __launch_bounds__(kThreads) void decode_valu_kernel(const DecodeParams p)
 {
     constexpr int LPT = D / 8;          // lanes per token row
@@ -60,31 +99,30 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(const DecodeParam
     }
 
     const int64_t tok_stride = (int64_t)Hkv * D; // elements between tokens of a page
-    const uint16_t *kc = (const uint16_t *)p.k_cache;
-    const uint16_t *vc = (const uint16_t *)p.v_cache;
     const int32_t *bt = p.block_table + (int64_t)b * p.max_pages;
     const int pg_end = (t1 + kPageSize - 1) / kPageSize;
 
     for (int pg = t0 / kPageSize + wave; pg < pg_end; pg += kWaves) {
         const int page = clamp_page(bt[pg], p.num_pages);
         const int64_t base = ((int64_t)page * kPageSize * Hkv + kvh) * D + c * 8;
-        u32x4 kr[U], vr[U];
+        Row8<FP8> kr[U], vr[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            kr[u] = *(const u32x4 *)(kc + base + (u * TPL + j) * tok_stride);
+            kr[u].load(p.k_cache, base + (u * TPL + j) * tok_stride);
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            vr[u] = *(const u32x4 *)(vc + base + (u * TPL + j) * tok_stride);
+            vr[u].load(p.v_cache, base + (u * TPL + j) * tok_stride);
+        float k_scale = 1.f, v_scale = 1.f;
+        if (FP8) {
+            k_scale = p.k_scale[(int64_t)page * Hkv + kvh];
+            v_scale = p.v_scale[(int64_t)page * Hkv + kvh];
+        }
 
         float s[U][G];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float kf[8];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                kf[2 * e] = bf16_lo(kr[u][e]);
-                kf[2 * e + 1] = bf16_hi(kr[u][e]);
-            }
+            kr[u].widen(kf);
             const bool valid = pg * kPageSize + u * TPL + j < t1;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
@@ -93,11 +131,17 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(const DecodeParam
                 for (int e = 0; e < 8; ++e)
                     dot = fmaf(qf[g][e], kf[e], dot);
                 dot = group_sum<LPT>(dot);
+                if (FP8)
+                    dot *= k_scale;
                 s[u][g] = valid ? dot : -INFINITY; // select, so garbage in unwritten slots never spreads
             }
             if (!valid)
-                vr[u] = u32x4{0u, 0u, 0u, 0u};
+                vr[u].clear();
         }
+        float vf[U][8];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            vr[u].widen(vf[u]);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             float mn = m[g];
@@ -113,14 +157,17 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(const DecodeParam
                 ps += pw[u];
             }
             l[g] = l[g] * alpha + ps;
+            if (FP8) {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    pw[u] *= v_scale;
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 float acc = o[g][e] * alpha;
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t w = vr[u][e >> 1];
-                    acc = fmaf(pw[u], (e & 1) ? bf16_hi(w) : bf16_lo(w), acc);
-                }
+                for (int u = 0; u < U; ++u)
+                    acc = fmaf(pw[u], vf[u][e], acc);
                 o[g][e] = acc;
             }
         }
@@ -169,11 +216,14 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(const DecodeParam
 
 #define ADR_VALU_CASE(DD, GG)                                                                     \
     if (d == DD && G == GG) {                                                                     \
-        decode_valu_kernel<DD, GG><<<grid, kThreads, 0, stream>>>(p);                             \
+        if (fp8)                                                                                  \
+            decode_valu_kernel<DD, GG, true><<<grid, kThreads, 0, stream>>>(p);                   \
+        else                                                                                      \
+            decode_valu_kernel<DD, GG, false><<<grid, kThreads, 0, stream>>>(p);                  \
         return hipGetLastError();                                                                 \
     }
 
-hipError_t launch_decode_valu(const DecodeParams &p, int d, hipStream_t stream)
+hipError_t launch_decode_valu(const DecodeParams &p, int d, bool fp8, hipStream_t stream)
 {
     const int G = p.G;
     const dim3 grid((unsigned)((int64_t)p.B * p.Hkv * p.max_parts));

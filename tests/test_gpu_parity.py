@@ -211,3 +211,75 @@ def test_split_equals_unsplit_within_rounding():
         split, ls = gpu_attention(*args, partition_tokens=part)
         assert (whole - split).abs().max().item() < 2e-5
         assert (lw - ls).abs().max().item() < 2e-5
+
+
+# ---- fp8-e4m3 cache -----------------------------------------------------------------
+
+def fp8_case(seed, Hq, Hkv, d, lens):
+    """A small case whose caches are quantised on the host (library casts only); the oracle
+    reads the dequantised values, so only the attention arithmetic is under test."""
+    b = small_case(seed, Hq, Hkv, d, lens)
+    k8, ks = W.quantize_pool_fp8(b.k_cache, b.used)
+    v8, vs = W.quantize_pool_fp8(b.v_cache, b.used)
+    return b, k8, ks, v8, vs
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma", "auto"])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 8, 128), (8, 2, 128), (32, 8, 128), (16, 1, 128),
+                                      (8, 8, 64), (8, 2, 64)])
+@pytest.mark.parametrize("partition_tokens", [0, 64, 512])
+def test_fp8_cache_attention_matches_oracle(kernel, Hq, Hkv, d, partition_tokens):
+    if kernel == "mfma" and d != 128:
+        pytest.skip("the matrix-core kernel covers d = 128")
+    if kernel == "valu" and Hq // Hkv == 16:
+        pytest.skip("the vector-ALU kernel covers groups of 1, 2, 4 and 8")
+    b, k8, ks, v8, vs = fp8_case(60 + Hq + Hkv, Hq, Hkv, d, [L - 1 for L in LENS] + [0])
+    seq = b.seq_lens.copy()
+    seq[-1] = 0
+    say("fp8 parity kernel=%s Hq=%d Hkv=%d d=%d part=%d" % (kernel, Hq, Hkv, d, partition_tokens))
+    out, lse = gpu_attention(dev(b.q), dev(k8), dev(v8), dev(b.block_table), dev(seq), b.wl.scale,
+                             partition_tokens=partition_tokens, flags=KERNELS[kernel],
+                             k_scale=dev(ks), v_scale=dev(vs))
+    ref, ref_lse, _ = oracle.decode_attention(W.bits(b.q), W.bits(k8), W.bits(v8), b.block_table, seq,
+                                              b.wl.scale, k_scale=W.bits(ks), v_scale=W.bits(vs))
+    max_abs, _ = compare(out, lse, ref, ref_lse, what="fp8 %s %d/%d/%d" % (kernel, Hq, Hkv, d))
+    assert max_abs <= ATOL
+    assert torch.all(out[-1] == 0) and torch.isneginf(lse[-1]).all()
+
+
+def test_fp8_grid_kernel_is_reported_unsupported():
+    b, k8, ks, v8, vs = fp8_case(61, 8, 2, 128, [40, 7])
+    with pytest.raises(adr.AdrError):
+        gpu_attention(dev(b.q), dev(k8), dev(v8), dev(b.block_table), dev(b.seq_lens), b.wl.scale,
+                      flags=adr.KERNEL_MFMA_GRID, k_scale=dev(ks), v_scale=dev(vs))
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_fp8_append_is_byte_exact_then_attend(d):
+    """Append into an fp8 cache (slot 0 sets the page's scale, other slots reuse it and saturate),
+    whole pool and both scale arrays byte for byte against the oracle's rule, then attend."""
+    lens = [0, 1, 15, 16, 17, 32, 100, 255, 256]      # slot 0 (new page) and mid-page slots
+    b, k8, ks, v8, vs = fp8_case(62 + d, 8, 2, d, lens)
+    # a new token several times larger than the page's content: saturates where the scale is reused
+    b.k_new[2] *= 6.0
+    b.v_new[6] *= 6.0
+    pos = b.positions.copy()
+    pos[7] = -1                                        # a skipped row
+    kd, vd, ksd, vsd = dev(k8), dev(v8), dev(ks), dev(vs)
+    say("fp8 append d=%d" % d)
+    adr.adr_kv_append(adr.KVCache(kd, vd, ksd, vsd), dev(b.k_new), dev(b.v_new), dev(b.block_table), dev(pos))
+    torch.cuda.synchronize()
+    kh, vh, ksh, vsh = (W.bits(t).copy() for t in (k8, v8, ks, vs))
+    oracle.kv_append(kh, vh, W.bits(b.k_new), W.bits(b.v_new), b.block_table, pos, k_scale=ksh, v_scale=vsh)
+    assert np.array_equal(W.bits(kd), kh) and np.array_equal(W.bits(vd), vh)
+    assert np.array_equal(W.bits(ksd).view(np.uint32), ksh.view(np.uint32))
+    assert np.array_equal(W.bits(vsd).view(np.uint32), vsh.view(np.uint32))
+
+    seq = b.seq_lens.copy()
+    seq[7] -= 1
+    for kernel in ("valu", "mfma") if d == 128 else ("valu",):
+        out, lse = gpu_attention(dev(b.q), kd, vd, dev(b.block_table), dev(seq), b.wl.scale,
+                                 flags=KERNELS[kernel], k_scale=ksd, v_scale=vsd)
+        ref, ref_lse, _ = oracle.decode_attention(W.bits(b.q), kh, vh, b.block_table, seq, b.wl.scale,
+                                                  k_scale=ksh, v_scale=vsh)
+        assert compare(out, lse, ref, ref_lse, what="fp8 append+attend %s" % kernel)[0] <= ATOL
