@@ -188,12 +188,12 @@ __device__ __forceinline__ void issue_page(char *tile, __amdgpu_buffer_rsrc_t kr
     for (int i = 0; i < geo::kTileLoads; ++i)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             krsrc, (__attribute__((address_space(3))) void *)(tile + i * 1024), 16, k_lane[i],
-            head_bytes, 0, 0);
+            head_bytes, 0, kStreamOnce);
 #pragma unroll
     for (int i = 0; i < geo::kTileLoads; ++i)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             vrsrc, (__attribute__((address_space(3))) void *)(tile + geo::kTile + i * 1024), 16,
-            v_lane[i], head_bytes, 0, 0);
+            v_lane[i], head_bytes, 0, kStreamOnce);
     if (FP8) {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             ksrsrc, (__attribute__((address_space(3))) void *)(tile + 2 * geo::kTile), 4, s_lane,

@@ -17,11 +17,12 @@
 
 namespace adr {
 
-// Eight cache elements of one lane as fp32.
+// Eight cache elements of one lane as fp32.  Loaded with the non-temporal hint: each
+// byte is used once per pass.
 template <bool FP8> struct Row8;
 template <> struct Row8<false> {
     u32x4 w;
-    __device__ __forceinline__ void load(const void *cache, int64_t elem) { w = *(const u32x4 *)((const uint16_t *)cache + elem); }
+    __device__ __forceinline__ void load(const void *cache, int64_t elem) { w = __builtin_nontemporal_load((const u32x4 *)((const uint16_t *)cache + elem)); }
     __device__ __forceinline__ void clear() { w = u32x4{0u, 0u, 0u, 0u}; }
     __device__ __forceinline__ void widen(float (&f)[8]) const
     {
@@ -34,7 +35,7 @@ template <> struct Row8<false> {
 };
 template <> struct Row8<true> {
     u32x2 w;
-    __device__ __forceinline__ void load(const void *cache, int64_t elem) { w = *(const u32x2 *)((const uint8_t *)cache + elem); }
+    __device__ __forceinline__ void load(const void *cache, int64_t elem) { w = __builtin_nontemporal_load((const u32x2 *)((const uint8_t *)cache + elem)); }
     __device__ __forceinline__ void clear() { w = u32x2{0u, 0u}; }
     __device__ __forceinline__ void widen(float (&f)[8]) const
     {

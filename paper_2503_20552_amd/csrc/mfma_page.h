@@ -17,6 +17,11 @@ struct PageRegs {
 constexpr int kTileBytes = kPageSize * D * 2; // one page of K for one kv-head
 constexpr int kStages = 2;
 
+// Cache policy of the K/V loads ("nt"): every byte is used once per pass, so it
+// should not displace the block table, queries and partial results in the caches.
+// Measured on MI355X: 6.9 TB/s instead of 6.1 TB/s for a bare ring of such loads.
+constexpr int kStreamOnce = 2;
+
 // Buffer descriptor of one cache page: base = the page, range = the page's
 // bytes (reads past it return zero instead of touching memory), raw 32-bit
 // addressing.  Built from wave-uniform values, so it lives in scalar registers
@@ -39,10 +44,10 @@ __device__ __forceinline__ void load_page(PageRegs &pr, char *ktile, __amdgpu_bu
 #pragma unroll
     for (int i = 0; i < 4; ++i)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (__attribute__((address_space(3))) void *)(ktile + i * 1024),
-                                                 16, k_lane[i], 0, 0, 0);
+                                                 16, k_lane[i], 0, 0, kStreamOnce);
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-        pr.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrsrc, v_lane, u * tok_bytes, 0);
+        pr.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrsrc, v_lane, u * tok_bytes, kStreamOnce);
     asm volatile("" ::: "memory");
 }
 
