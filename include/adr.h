@@ -180,6 +180,15 @@ int adr_lse_merge(void *out, adr_dtype out_dtype, float *lse_out, const float *p
 int adr_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream);
 int adr_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/*
+ * Self-check of the resident-workgroup kernel (ADR_KERNEL_MFMA): its waves hand
+ * work to each other through flags in on-chip memory, and every wait on such a
+ * flag is bounded.  `*count` (a HOST pointer) receives the number of waits that
+ * expired on the current device since the library was loaded; anything but 0
+ * means results of that kernel cannot be trusted.  Synchronises the device.
+ */
+int adr_stream_fault_count(uint64_t *count);
+
 const char *adr_status_string(int status);
 int adr_version(void);
 

@@ -17,7 +17,7 @@ PARTIALS_ONLY = 16
 
 EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention",
            "adr_decode_merge", "adr_lse_merge", "adr_probe_stream_read", "adr_probe_copy",
-           "adr_status_string", "adr_version")
+           "adr_stream_fault_count", "adr_status_string", "adr_version")
 
 
 class AdrError(RuntimeError):
@@ -67,12 +67,21 @@ def load_library():
     lib.adr_probe_stream_read.argtypes = [vp, sz, vp, vp]
     lib.adr_probe_copy.restype = i32
     lib.adr_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.adr_stream_fault_count.restype = i32
+    lib.adr_stream_fault_count.argtypes = [ctypes.POINTER(ctypes.c_uint64)]
     lib.adr_status_string.restype = ctypes.c_char_p
     lib.adr_status_string.argtypes = [i32]
     lib.adr_version.restype = i32
     lib.adr_version.argtypes = []
     _lib = lib
     return lib
+
+
+def adr_stream_fault_count() -> int:
+    """Expired waits inside the resident-workgroup kernel on the current device (0 when healthy)."""
+    n = ctypes.c_uint64(0)
+    _check(load_library().adr_stream_fault_count(ctypes.byref(n)), "adr_stream_fault_count")
+    return int(n.value)
 
 
 def adr_status_string(status: int) -> str:

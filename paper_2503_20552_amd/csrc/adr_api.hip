@@ -8,6 +8,7 @@ hipError_t launch_kv_append(const AppendParams &p, bool fp8, hipStream_t stream)
 hipError_t launch_decode_valu(const DecodeParams &p, int d, bool fp8, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeParams &p, int d, hipStream_t stream);
 hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStream_t stream);
+hipError_t read_stream_faults(unsigned long long *count);
 bool decode_stream_supports(int d, int G, int B);
 bool decode_valu_supports(int d, int G);
 bool decode_mfma_supports(int d, int G);
@@ -52,6 +53,17 @@ size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 extern "C" {
 
 int adr_version(void) { return 100; }
+
+int adr_stream_fault_count(uint64_t *count)
+{
+    if (!count)
+        return ADR_ERR_NULL;
+    unsigned long long n = 0;
+    if (adr::read_stream_faults(&n) != hipSuccess)
+        return ADR_ERR_LAUNCH;
+    *count = (uint64_t)n;
+    return ADR_OK;
+}
 
 const char *adr_status_string(int status)
 {

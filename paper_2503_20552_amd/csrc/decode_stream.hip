@@ -1,43 +1,47 @@
 // Persistent matrix-core decode attention (d = 128, bf16 or fp8-e4m3 cache, G <= 16,
 // B <= 512).
 //
-// The grid is a fixed number of workgroups (a couple per compute unit) that
-// stay resident and pull work items from a ticket counter until none is left.
-// An item is one (request, partition, kv-head); the four waves of a workgroup
-// share it, wave w streaming pages w, w+4, ... of the partition, exactly as in
-// decode_mfma.hip.  What changes is everything around the page loop:
+// The grid is one workgroup of four waves per compute unit.  The workgroups stay
+// resident and pull work items from a ticket counter until none is left.  An
+// item is one (request, partition, kv-head); the four waves share it, wave w
+// taking pages w, w+4, ... of the partition.  Apart from that shared result the
+// waves run on their own: there is no barrier in the item loop.
 //
-//  * No empty workgroups.  Every workgroup first scans seq_lens into two
-//    prefix arrays in LDS (full partitions per row, ragged last partitions per
-//    row); ticket t is decoded by binary search.  Tickets enumerate all full
-//    partitions first and the ragged ones last, so the work that is handed out
-//    at the very end is the small pieces.
-//  * No pipeline drain between items.  A wave's page stream runs across item
-//    boundaries: while the last page of an item is consumed, the first page of
-//    the next item is already in flight, and the next item's query is loaded
-//    one item ahead.  Tickets are drawn two items ahead for that reason.
-//  * K and V tiles both arrive by direct-to-LDS loads into a ring of S stages per
-//    wave (K rows XOR-swizzled for the operand reads, V rows natural); S - 1
-//    pages are in flight while one is consumed.  One workgroup per compute
-//    unit owns (almost) its whole LDS, which is what pays for the deep ring:
-//    the loads in flight keep the memory pipes fed while the waves of the
-//    workgroup meet at an item's end.  The ring position is a run-time value.
-//    A wave whose stream has run dry (no further page in the current or the
-//    next item) fills ring slots with null loads, so the number of load groups
-//    in flight never changes and one wait count serves every page; null slots
-//    are skipped when their turn comes.
-//  * The query operand of an item is likewise staged in LDS (one 16-row tile per
-//    workgroup, fetched by wave 0 one item ahead), so no load into registers is
-//    ever pending inside the page loop and the compiler adds no waits there.
-//  * The cross-wave combination of an item goes through a double-buffered
-//    staging area, so one barrier per item is enough.
+//  * No empty workgroups.  Every workgroup first scans seq_lens into two prefix
+//    arrays in LDS (full partitions per row, ragged last partitions per row);
+//    ticket t is decoded by binary search.  Tickets enumerate all full
+//    partitions first and the ragged ones last, so the work handed out at the
+//    very end is the small pieces.
+//  * Items are announced through a small queue of records in LDS.  The ticket of
+//    item k+3 is drawn at the start of item k by wave k mod 4, which decodes and
+//    publishes it when it has finished its share of item k; every wave picks a
+//    record up one item before it becomes its "next" item.  A record's sequence
+//    stamp is written last; readers poll it.
+//  * A wave's page stream runs across item boundaries.  K and V tiles arrive by
+//    direct-to-LDS loads into a ring of S stages per wave (K rows XOR-swizzled
+//    for the operand reads, V rows natural).  The ring is kept full; a wave
+//    whose stream has run dry fills slots with null loads, so the number of load
+//    groups in flight is always known and plain wait counts serve every page.
+//    Null slots are passed over when they reach the head of the ring.
+//  * Pages are consumed two at a time when the wave's next two pages are both in
+//    the ring: one softmax step over 32 tokens, and P V as 16x16x32 products.
+//  * Each wave fetches the query rows of its next item into a tile of its own
+//    (direct-to-LDS as well, one item ahead), so no load into registers is ever
+//    pending inside the page loop and the compiler adds no waits there.
+//  * The per-wave results of an item meet in a staging buffer (two buffers,
+//    used alternately).  Each wave adds itself to the buffer's arrival counter;
+//    the wave that arrives last combines the four results, writes the output and
+//    hands the buffer back.  Nobody else waits.
 //
 // fp8 cache: a page of one kv-head is half the bytes (two loads per tile instead
 // of four), and two more 4-byte direct-to-LDS loads bring the page's K and V
 // scales into the tail of the ring stage.  The bytes are widened to bf16 (exact)
 // after the LDS read and enter the same matrix instructions; the K scale is
-// folded into the score scale and the V scale into the weights.  The ring is
-// deeper, since a stage is smaller.
+// folded into the score scale and the V scale into the weights.
+//
+// Every wait on another wave is bounded: a wave that has polled an LDS word for
+// far longer than any legitimate delay raises a fault counter (readable through
+// adr_stream_fault_count) and carries on, so the grid always drains.
 //
 // The ticket counter and a finished-workgroups counter live in a small pool of
 // static device words that are zero whenever no launch is using them: the last
@@ -51,6 +55,9 @@ namespace adr {
 
 constexpr int kMaxStreamB = 512;
 constexpr int kTicketSlots = 64;
+constexpr int kQueue = 8;          // item records kept in LDS (power of two)
+constexpr int kSpinLimit = 1 << 20; // polls of an LDS word before a wait is declared failed (~0.1 s)
+constexpr int kSpinLimitAfterFault = 64; // ... once a wait of this workgroup has failed
 
 // Geometry of one ring stage: K tile, V tile, then (fp8) the two scales, each
 // in a 256-byte slot of its own (a 4-byte direct-to-LDS load covers 64 x 4 bytes).
@@ -65,34 +72,45 @@ template <bool FP8> struct Geo {
 };
 
 __device__ uint32_t g_tickets[kTicketSlots][2];
+__device__ unsigned long long g_stream_faults;
 
 struct StreamParams {
     DecodeParams d;
     uint32_t *ticket; // {next ticket, workgroups finished}
+    unsigned long long *faults;
     int pt;           // tokens per partition (2^30 when the pass is not split)
     int stages;       // ring stages per wave (2 .. Geo::kMaxStages)
+    int nb;           // staging buffers (1 or 2)
+    int q_rows;       // rows of a wave's query tile (G rounded up to 4)
 };
 
+// One work item as the queue carries it (all fields wave-uniform).
 struct Item {
     int valid;
     int b, kvh, part;
     int t1;      // end of the token range (exclusive); the range starts at part * pt
     int n_parts; // partitions of the row (1: write the final result directly)
-    int pg;      // first page of this wave
-    int pg_end;  // one past the last page of the item
+};
+
+struct Rec {
+    int seq; // index of the item this record describes; written last
+    int valid, b, kvh, part, t1, n_parts, pad;
 };
 
 typedef const __attribute__((address_space(4))) int32_t *table_ptr;
 
-constexpr int kMaxLdsBytes = 160 * 1024;  // LDS of one compute unit
-constexpr int kQTileBytes = 16 * D * 2; // sixteen query rows (heads of a group, zero beyond G)
+constexpr int kMaxLdsBytes = 160 * 1024; // LDS of one compute unit
 
-// LDS layout: the ring (kWaves * stages * Geo::kStage), this block, then the
-// staging area float[2][kWaves][G][D] for the per-wave results of an item.
-struct Shared {
-    char qtile[2][kQTileBytes]; // query tile of the current / the next item, rows swizzled like K
-    float ml[2][kWaves][16][2]; // per item parity, per wave: running max, denominator of each head
-    int slot[2];                // tickets of the items after the current one
+// LDS layout: the ring (kWaves * stages * Geo::kStage), the query tiles
+// (kWaves * 2 * q_rows * 256 bytes), this block, then the staging area
+// float[nb][kWaves][G][D] for the per-wave results of an item.
+struct alignas(16) Shared {
+    Rec rec[kQueue];
+    int gen[2];    // per staging buffer: how many items have been combined out of it
+    int arrive[2]; // per staging buffer: waves that have delivered the current item
+    int first[3];  // tickets of the first three items
+    int failed;    // a bounded wait of this workgroup has expired
+    float ml[2][kWaves][16][2]; // per staging buffer, per wave: running max, denominator of each head
     int wave_tot[2][kWaves];
     int total[2];
     int pref_full[kMaxStreamB + 1];
@@ -114,8 +132,7 @@ __device__ __forceinline__ int find_row(const int *pref, int B, int u)
     return lo;
 }
 
-__device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamParams &sp, int ticket,
-                                              int wave)
+__device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamParams &sp, int ticket)
 {
     Item it;
     const int Hkv = sp.d.Hkv, B = sp.d.B;
@@ -124,7 +141,7 @@ __device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamPara
     const int total_full = __builtin_amdgcn_readfirstlane(sh.total[0]);
     const int total_rag = __builtin_amdgcn_readfirstlane(sh.total[1]);
     it.valid = (unsigned)ticket < (unsigned)((total_full + total_rag) * Hkv);
-    it.b = it.kvh = it.part = it.t1 = it.pg = it.pg_end = 0;
+    it.b = it.kvh = it.part = it.t1 = 0;
     it.n_parts = 1;
     if (it.valid) {
         const int unit = ticket / Hkv;
@@ -146,17 +163,98 @@ __device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamPara
         it.t1 = __builtin_amdgcn_readfirstlane(t1);
         const int np = L > 0 ? (L - 1) / sp.pt + 1 : 1;
         it.n_parts = __builtin_amdgcn_readfirstlane(np);
-        // part * pt cannot overflow: when the pass is not split, part is 0
-        it.pg = it.part * (sp.pt / kPageSize) + wave;
-        it.pg_end = (it.t1 + kPageSize - 1) / kPageSize;
     }
     return it;
 }
 
-// Fetch the query tile of one item into LDS (one wave calls this): sixteen rows
-// of 256 bytes, row t stored with its chunks XOR-permuted by t exactly like a K
-// tile.  The descriptor spans the G rows of the group; rows beyond it are out of
-// range (their content is never used: they only feed score columns >= G).
+// The flags the waves exchange live in LDS, and the LDS executes one wave's
+// accesses in the order they were issued.  So a flag written after the data it
+// guards is seen after that data, and data read after a flag was seen is at
+// least as new as the flag: nothing but the compiler has to be kept from
+// reordering.  (Acquire/release atomics would also wait for the page loads in
+// flight, which is exactly what the ring must not do.)
+//
+// The flag accesses are written as instructions by hand: the compiler would
+// otherwise guard an atomic LDS access with a wait for all direct-to-LDS loads.
+__device__ __forceinline__ void lds_order() { asm volatile("" ::: "memory"); }
+
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
+}
+
+__device__ __forceinline__ int flag_read(const int *word)
+{
+    int v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(lds_address(word)) : "memory");
+    return v;
+}
+
+__device__ __forceinline__ void flag_write(int *word, int value)
+{
+    asm volatile("ds_write_b32 %0, %1" ::"v"(lds_address(word)), "v"(value) : "memory");
+}
+
+__device__ __forceinline__ int flag_add(int *word, int value)
+{
+    int old;
+    asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(old)
+                 : "v"(lds_address(word)), "v"(value)
+                 : "memory");
+    return old;
+}
+
+// Poll an LDS word until it holds `want`.  Returns false (and counts a fault)
+// when it never does; the caller then goes on without what it waited for.
+__device__ __forceinline__ bool poll_equal(int *word, int want, int *failed, unsigned long long *faults)
+{
+    const int limit = __builtin_amdgcn_readfirstlane(flag_read(failed)) ? kSpinLimitAfterFault : kSpinLimit;
+    for (int spin = 0; spin < limit; ++spin) {
+        if (__builtin_amdgcn_readfirstlane(flag_read(word)) == want) {
+            lds_order();
+            return true;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        flag_write(failed, 1);
+        atomicAdd(faults, 1ull);
+    }
+    return false;
+}
+
+__device__ __forceinline__ void publish(Rec &rec, const Item &it, int seq)
+{
+    if ((threadIdx.x & 63) == 0) {
+        rec.valid = it.valid;
+        rec.b = it.b;
+        rec.kvh = it.kvh;
+        rec.part = it.part;
+        rec.t1 = it.t1;
+        rec.n_parts = it.n_parts;
+        lds_order();
+        flag_write(&rec.seq, seq);
+    }
+}
+
+__device__ __forceinline__ Item fetch(Rec &rec, int seq, int *failed, unsigned long long *faults)
+{
+    Item it;
+    const bool ok = poll_equal(&rec.seq, seq, failed, faults);
+    it.valid = ok ? __builtin_amdgcn_readfirstlane(rec.valid) : 0;
+    it.b = __builtin_amdgcn_readfirstlane(rec.b);
+    it.kvh = __builtin_amdgcn_readfirstlane(rec.kvh);
+    it.part = __builtin_amdgcn_readfirstlane(rec.part);
+    it.t1 = __builtin_amdgcn_readfirstlane(rec.t1);
+    it.n_parts = __builtin_amdgcn_readfirstlane(rec.n_parts);
+    return it;
+}
+
+// Fetch the query rows of one item into this wave's LDS tile: rows of 256 bytes,
+// row t stored with its chunks XOR-permuted by t exactly like a K tile.  The
+// descriptor spans the G rows of the group; a row beyond it is out of range and
+// nobody reads it.
 __device__ __forceinline__ void issue_query(char *qtile, const StreamParams &sp, const Item &it,
                                             const uint32_t (&q_lane)[4])
 {
@@ -167,8 +265,9 @@ __device__ __forceinline__ void issue_query(char *qtile, const StreamParams &sp,
     asm volatile("" ::: "memory");
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rs, (__attribute__((address_space(3))) void *)(qtile + i * 1024), 16, q_lane[i], 0, 0, 0);
+        if (4 * i < sp.q_rows)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rs, (__attribute__((address_space(3))) void *)(qtile + i * 1024), 16, q_lane[i], 0, 0, 0);
     asm volatile("" ::: "memory");
 }
 
@@ -205,46 +304,155 @@ __device__ __forceinline__ void issue_page(char *tile, __amdgpu_buffer_rsrc_t kr
     asm volatile("" ::: "memory");
 }
 
-// Workgroup barrier for the item loop: orders this wave's LDS accesses (they
-// complete in issue order once the LDS counter has drained) without waiting for
-// the direct-to-LDS page loads still in flight, which target ring stages that
-// no other wave ever touches.
-__device__ __forceinline__ void ring_barrier()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-// Wait until all but the newest S - 1 load groups have landed.
+// Wait until at most `groups` page-load groups (the newest ones) are still in
+// flight.  Loads return in order, so everything issued before them has landed.
 template <bool FP8>
-__device__ __forceinline__ void wait_ring(int stages)
+__device__ __forceinline__ void wait_groups(int groups)
 {
-#define ADR_WAIT_CASE(S)                                                                          \
-    case S:                                                                                       \
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 1) * Geo<FP8>::kGroup) : "memory");          \
+#define ADR_WAIT_CASE(N)                                                                          \
+    case N:                                                                                       \
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N * Geo<FP8>::kGroup) : "memory");                \
         break;
-    switch (stages) {
+    switch (groups) {
         ADR_WAIT_CASE(6)
         ADR_WAIT_CASE(5)
         ADR_WAIT_CASE(4)
         ADR_WAIT_CASE(3)
-    default:
         ADR_WAIT_CASE(2)
+        ADR_WAIT_CASE(1)
+    default:
+        ADR_WAIT_CASE(0)
     }
 #undef ADR_WAIT_CASE
+}
+
+// Two pages at once (page A = tokens tok .. , page B = the wave's next page, 64
+// tokens further on): S = K Q^T for both, one online-softmax step over the 32
+// tokens, O += P V with the contraction running over both pages.  Only B can be
+// the partition's last, partly filled page.
+__device__ __forceinline__ void attend_pair(WaveState &st, PageRegs &pa, PageRegs &pb,
+                                            const u32x4 (&ka)[4], const u32x4 (&kb)[4],
+                                            const u32x4 (&qb)[4], float score_a, float score_b,
+                                            float p_scale_a, float p_scale_b, int tok_b, int t1, int j)
+{
+    f32x4 sa = f32x4{0.f, 0.f, 0.f, 0.f}, sb = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kk]),
+                                                     __builtin_bit_cast(bf16x8, qb[kk]), sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[kk]),
+                                                     __builtin_bit_cast(bf16x8, qb[kk]), sb, 0, 0, 0);
+    }
+    // tok_b = index of the first of this lane's four tokens in page B
+    const bool tail = tok_b - 4 * j + kPageSize > t1;
+    float sc[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        sc[i] = sa[i] * score_a;
+        sc[4 + i] = sb[i] * score_b;
+        if (tail && tok_b + i >= t1)
+            sc[4 + i] = -INFINITY;
+    }
+    if (tail) { // rows of tokens past the end may hold anything: keep them out of P*V
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (tok_b + u >= t1)
+                pb.v[u] = u32x4{0u, 0u, 0u, 0u};
+    }
+
+    float bm = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
+                     fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+    bm = fmaxf(bm, __shfl_xor(bm, 16));
+    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    if (__any(bm > st.m)) {
+        const float mn = fmaxf(st.m, bm);
+        const float alpha = fast_exp2(st.m - mn);
+        st.m = mn;
+        st.l *= alpha;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float a = __shfl(alpha, 4 * j + i);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                st.o[e][i] *= a;
+        }
+    }
+    uint32_t ph[8], pl[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float pw = fast_exp2(sc[i] - st.m);
+        st.l += pw;
+        pw *= i < 4 ? p_scale_a : p_scale_b;
+        ph[i] = __float_as_uint(pw) & 0xffff0000u;            // bf16 head (truncated)
+        pl[i] = __float_as_uint(pw - __uint_as_float(ph[i])); // remainder, exact in fp32
+    }
+    u32x4 ah, al; // eight bf16 each: elements 0..3 <-> page A tokens 4j+i, 4..7 <-> page B tokens 4j+i
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        ah[h] = (ph[2 * h] >> 16) | ph[2 * h + 1];
+        al[h] = (pl[2 * h] >> 16) | (pl[2 * h + 1] & 0xffff0000u);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        u32x4 vb;
+        vb[0] = __builtin_amdgcn_perm(pa.v[1][e >> 1], pa.v[0][e >> 1], sel);
+        vb[1] = __builtin_amdgcn_perm(pa.v[3][e >> 1], pa.v[2][e >> 1], sel);
+        vb[2] = __builtin_amdgcn_perm(pb.v[1][e >> 1], pb.v[0][e >> 1], sel);
+        vb[3] = __builtin_amdgcn_perm(pb.v[3][e >> 1], pb.v[2][e >> 1], sel);
+        st.o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+            __builtin_bit_cast(bf16x8, ah), __builtin_bit_cast(bf16x8, vb), st.o[e], 0, 0, 0);
+        st.o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+            __builtin_bit_cast(bf16x8, al), __builtin_bit_cast(bf16x8, vb), st.o[e], 0, 0, 0);
+    }
+}
+
+// Read one ring stage into operand registers (widening an fp8 page to bf16).
+template <bool FP8>
+__device__ __forceinline__ void read_stage(const char *tile, const uint32_t (&k_read)[4], uint32_t v_read,
+                                           PageRegs &pr, u32x4 (&ka)[4], float &k_scale, float &v_scale)
+{
+    typedef Geo<FP8> geo;
+    if (FP8) {
+        u32x2 vraw[4], kraw[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            vraw[u] = *(const u32x2 *)(tile + geo::kTile + v_read + u * geo::kRow);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            kraw[kk] = *(const u32x2 *)(tile + k_read[kk]);
+        k_scale = *(const float *)(tile + 2 * geo::kTile);
+        v_scale = *(const float *)(tile + 2 * geo::kTile + geo::kScaleSlot);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            pr.v[u] = fp8x8_to_bf16x8(vraw[u]);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            ka[kk] = fp8x8_to_bf16x8(kraw[kk]);
+    } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            pr.v[u] = *(const u32x4 *)(tile + geo::kTile + v_read + u * geo::kRow);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            ka[kk] = *(const u32x4 *)(tile + k_read[kk]);
+        k_scale = v_scale = 1.f;
+    }
 }
 
 template <bool FP8>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 2)))
 void decode_stream_kernel(const StreamParams sp)
 {
-    const DecodeParams &p = sp.d;
     typedef Geo<FP8> geo;
     constexpr int kStageBytes = geo::kStage;
+    const DecodeParams &p = sp.d;
     const int S = sp.stages;
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     const int ring_bytes = kWaves * S * kStageBytes;
-    Shared &sh = *(Shared *)(lds_raw + ring_bytes);
-    float *staging = (float *)(lds_raw + ring_bytes + sizeof(Shared)); // [2][kWaves][G][D]
+    const int qtile_bytes = sp.q_rows * (D * 2);
+    Shared &sh = *(Shared *)(lds_raw + ring_bytes + kWaves * 2 * qtile_bytes);
+    float *staging = (float *)((char *)&sh + sizeof(Shared)); // [nb][kWaves][G][D]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -283,6 +491,13 @@ void decode_stream_kernel(const StreamParams sp)
             sh.wave_tot[0][wave] = xf;
             sh.wave_tot[1][wave] = xg;
         }
+        if (tid < kQueue)
+            sh.rec[tid].seq = -1;
+        if (tid == 0) {
+            sh.gen[0] = sh.gen[1] = 0;
+            sh.arrive[0] = sh.arrive[1] = 0;
+            sh.failed = 0;
+        }
         __syncthreads();
         int bf = 0, bg = 0, tf = 0, tg = 0;
 #pragma unroll
@@ -310,9 +525,13 @@ void decode_stream_kernel(const StreamParams sp)
             sh.pref_rag[B] = tg;
             sh.total[0] = tf;
             sh.total[1] = tg;
-            sh.slot[0] = (int)atomicAdd(sp.ticket, 1u);
-            sh.slot[1] = (int)atomicAdd(sp.ticket, 1u);
+            sh.first[0] = (int)atomicAdd(sp.ticket, 1u);
+            sh.first[1] = (int)atomicAdd(sp.ticket, 1u);
+            sh.first[2] = (int)atomicAdd(sp.ticket, 1u);
         }
+        __syncthreads();
+        if (wave < 3)
+            publish(sh.rec[wave], decode_ticket(sh, sp, sh.first[wave]), wave);
         __syncthreads();
     }
 
@@ -323,12 +542,13 @@ void decode_stream_kernel(const StreamParams sp)
     //       holds chunk c ^ (t & 7).  The same 8 elements are the 8-byte piece kk*4 + j.
     const uint32_t tok_bytes = (uint32_t)Hkv * geo::kRow;
     const uint32_t page_bytes = kPageSize * tok_bytes;
+    const int rq = r < G ? r : 0; // query row this lane reads (columns >= G repeat head 0 and are never stored)
     uint32_t k_lane[4], v_lane[4], q_lane[4], k_read[4], q_read[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int t = 4 * i + j; // query-tile row this lane fetches in load i
         q_lane[i] = t * (D * 2) + ((r ^ t) * 16);
-        q_read[i] = r * (D * 2) + (((i * 4 + j) ^ r) * 16);
+        q_read[i] = rq * (D * 2) + (((i * 4 + j) ^ rq) * 16);
         if (FP8) {
             const int tf = 8 * (i & 1) + (lane >> 3), c = lane & 7; // row / slot of load i (i < 2)
             k_lane[i] = tf * tok_bytes + ((c ^ (tf & 7)) * 16);
@@ -338,7 +558,7 @@ void decode_stream_kernel(const StreamParams sp)
         } else {
             k_lane[i] = t * tok_bytes + ((r ^ t) * 16);
             v_lane[i] = t * tok_bytes + r * 16;
-            k_read[i] = q_read[i];
+            k_read[i] = r * (D * 2) + (((i * 4 + j) ^ r) * 16);
         }
     }
     // V operand: rows 4j + u, the 8 elements 8r .. 8r+7
@@ -347,27 +567,28 @@ void decode_stream_kernel(const StreamParams sp)
     const char *kc = (const char *)p.k_cache;
     const char *vc = (const char *)p.v_cache;
     char *ring = lds_raw + wave * (S * kStageBytes);
+    char *myq = lds_raw + ring_bytes + wave * (2 * qtile_bytes);
     const __amdgpu_buffer_rsrc_t null_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)kc, 0, 0, 0x00020000); // every read is out of range: zeros
     const int scale_range = FP8 ? p.num_pages * Hkv * 4 : 0;
-    const __amdgpu_buffer_rsrc_t ks_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(FP8 ? (const void *)p.k_scale : (const void *)kc), 0, scale_range, 0x00020000);
-    const __amdgpu_buffer_rsrc_t vs_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(FP8 ? (const void *)p.v_scale : (const void *)kc), 0, scale_range, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ks_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(FP8 ? (const void *)p.k_scale : (const void *)kc), 0, scale_range, 0x00020000);
+    const __amdgpu_buffer_rsrc_t vs_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(FP8 ? (const void *)p.v_scale : (const void *)kc), 0, scale_range, 0x00020000);
+    const int pages_per_part = sp.pt / kPageSize; // 2^26 when the pass is not split (part is 0 then)
 
-    Item C = decode_ticket(sh, sp, sh.slot[0], wave);
-    Item N = decode_ticket(sh, sp, sh.slot[1], wave);
-    if (wave == 0) {
-        issue_query(sh.qtile[0], sp, C, q_lane);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    __syncthreads();
+    Item C = fetch(sh.rec[0], 0, &sh.failed, sp.faults);
+    Item N = fetch(sh.rec[1], 1, &sh.failed, sp.faults);
+    issue_query(myq, sp, C, q_lane);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- load cursor: the next page of this wave's stream to be issued.  It runs
     // through the current item and on into the next one, never further.  It keeps
     // its own copy of what it needs from the item it is in.
+#define ADR_FIRST_PAGE(IT) ((IT).part * pages_per_part + wave)
+#define ADR_END_PAGE(IT) ((IT).valid ? ((IT).t1 + kPageSize - 1) / kPageSize : 0)
     int ld_in_next = 0;
-    int ld_pg = C.pg, ld_end = C.valid ? C.pg_end : 0;
+    int ld_pg = ADR_FIRST_PAGE(C), ld_end = ADR_END_PAGE(C);
     uint32_t ld_head = (uint32_t)C.kvh * geo::kRow;
     int ld_kvh = C.kvh;
     table_ptr ld_bt = (table_ptr)(p.block_table + (int64_t)C.b * p.max_pages);
@@ -376,8 +597,8 @@ void decode_stream_kernel(const StreamParams sp)
     do { /* move the cursor to the next existing page and fetch its page id */                    \
         if (!ld_in_next && ld_pg >= ld_end) {                                                     \
             ld_in_next = 1;                                                                       \
-            ld_pg = N.pg;                                                                         \
-            ld_end = N.valid ? N.pg_end : 0;                                                      \
+            ld_pg = ADR_FIRST_PAGE(N);                                                            \
+            ld_end = ADR_END_PAGE(N);                                                             \
             ld_head = (uint32_t)N.kvh * geo::kRow;                                                \
             ld_kvh = N.kvh;                                                                       \
             ld_bt = (table_ptr)(p.block_table + (int64_t)N.b * p.max_pages);                      \
@@ -386,49 +607,54 @@ void decode_stream_kernel(const StreamParams sp)
         if (ld_ok)                                                                                \
             ld_id = clamp_page(ld_bt[ld_pg], p.num_pages);                                        \
     } while (0)
-#define ADR_ISSUE(STAGE)                                                                          \
-    do { /* fill a ring stage with the cursor's page, or with a group of null loads */            \
-        const int stage_ = (STAGE);                                                               \
-        char *tile_ = ring + stage_ * kStageBytes;                                                \
+    // Ring state: `occ` slots starting at `head` are occupied, in issue order; the
+    // next load group goes to `tail`.  real_mask marks the slots that hold a page.
+    int head = 0, tail = 0, occ = 0, real_mask = 0;
+    int age = 0; // page-load groups issued since this item's look-ahead loads
+#define ADR_ISSUE()                                                                               \
+    do { /* fill the ring's tail slot with the cursor's page, or with a group of null loads */    \
+        char *tile_ = ring + tail * kStageBytes;                                                  \
         if (ld_ok) {                                                                              \
             issue_page<FP8>(tile_, page_rsrc(kc, ld_id, page_bytes),                              \
                             page_rsrc(vc, ld_id, page_bytes), ks_rsrc, vs_rsrc, k_lane, v_lane,   \
                             s_lane, ld_head, (uint32_t)(ld_id * Hkv + ld_kvh) * 4u);              \
-            real_mask |= 1 << stage_;                                                             \
+            real_mask |= 1 << tail;                                                               \
             ld_pg += kWaves;                                                                      \
             ADR_SETTLE();                                                                         \
         } else {                                                                                  \
             issue_page<FP8>(tile_, null_rsrc, null_rsrc, null_rsrc, null_rsrc, k_lane, v_lane,    \
                             s_lane, 0, 0);                                                        \
-            real_mask &= ~(1 << stage_);                                                          \
+            real_mask &= ~(1 << tail);                                                            \
         }                                                                                         \
+        tail = tail + 1 == S ? 0 : tail + 1;                                                      \
+        ++occ;                                                                                    \
+        ++age;                                                                                    \
     } while (0)
     ADR_SETTLE();
-    // Ring state: stages stage .. stage+S-2 (mod S) hold the next S-1 slots of the
-    // stream in order, stage-1 is free; real_mask marks the slots that hold a page.
-    int stage = 0, real_mask = 0;
-    for (int s0 = 0; s0 < S - 1; ++s0)
-        ADR_ISSUE(s0);
 
     uint32_t next_ticket = 0;
-    // Drawn once per item, after the item's first page has been consumed (so that
-    // nothing at the top of an item waits for these round trips): the ticket of the
-    // item after N, and N's query.  The counter's address may reach its scalar
-    // registers through a vector-lane read just before the statement; the five
-    // wait states such a value needs before a memory instruction may use it are
-    // not inserted around hand-written instructions, hence the s_nop.
-#define ADR_LOOK_AHEAD()                                                                          \
-    do {                                                                                          \
-        if (tid == 0)                                                                             \
-            asm volatile("s_nop 4\n\tglobal_atomic_add %0, %1, %2, %3 sc0"                        \
-                         : "=&v"(next_ticket)                                                     \
-                         : "v"(0), "v"(1), "s"(sp.ticket)                                         \
-                         : "memory");                                                             \
-        if (wave == 0)                                                                            \
-            issue_query(sh.qtile[(k + 1) & 1], sp, N, q_lane);                                    \
-    } while (0)
+    int invalid_run = 0;
+    // Tickets are drawn by four different waves at their own pace, so a ticket past
+    // the end can precede a valid one in the queue; each wave's own draws are in
+    // order, so four invalid records in a row mean the work is finished.
+    for (int k = 0;; ++k) {
+        invalid_run = C.valid ? 0 : invalid_run + 1;
+        if (invalid_run == kWaves)
+            break;
+        // ---- look-ahead loads: the query rows of the next item, and (one wave) the
+        // ticket of the item three ahead.  The counter's address may reach its scalar
+        // registers through a vector-lane read just before the statement; the five
+        // wait states such a value needs before a memory instruction may use it are
+        // not inserted around hand-written instructions, hence the s_nop.
+        const bool drawer = (k & (kWaves - 1)) == wave;
+        issue_query(myq + ((k + 1) & 1) * qtile_bytes, sp, N, q_lane);
+        if (drawer && lane == 0)
+            asm volatile("s_nop 4\n\tglobal_atomic_add %0, %1, %2, %3 sc0"
+                         : "=&v"(next_ticket)
+                         : "v"(0), "v"(1), "s"(sp.ticket)
+                         : "memory");
+        age = 0;
 
-    for (int k = 0; C.valid; ++k) {
         WaveState st;
 #pragma unroll
         for (int e = 0; e < 8; ++e)
@@ -438,128 +664,155 @@ void decode_stream_kernel(const StreamParams sp)
         u32x4 qb[4]; // B operand of QK^T: head r's query, chunk order matching the K reads
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-            qb[kk] = *(const u32x4 *)(sh.qtile[k & 1] + q_read[kk]);
+            qb[kk] = *(const u32x4 *)(myq + (k & 1) * qtile_bytes + q_read[kk]);
 
-        bool looked = false;
-        for (int pg = C.pg; pg < C.pg_end; pg += kWaves) {
-            // Step through the ring to the slot that holds this page: every step
-            // refills the stage freed by the step before; null slots are passed over.
-            for (;;) {
-                ADR_ISSUE(stage == 0 ? S - 1 : stage - 1);
-                if ((real_mask >> stage) & 1)
-                    break;
-                stage = stage + 1 == S ? 0 : stage + 1;
+        const int pg_end = ADR_END_PAGE(C);
+        for (int pg = ADR_FIRST_PAGE(C); pg < pg_end;) {
+            // Fill the ring, then pass over null slots at its head: each one frees a
+            // slot for the page the cursor now has.  The page wanted here is in the
+            // ring or at the cursor, so this ends after at most S steps.
+            while (occ < S)
+                ADR_ISSUE();
+            for (int guard = 0; !((real_mask >> head) & 1) && guard <= S; ++guard) {
+                head = head + 1 == S ? 0 : head + 1;
+                --occ;
+                ADR_ISSUE();
             }
-            wait_ring<FP8>(S);
-            const char *tile = ring + stage * kStageBytes;
-            PageRegs pr;
+            if (!((real_mask >> head) & 1)) { // cannot happen; never consume a slot that holds no page
+                if (lane == 0)
+                    atomicAdd(sp.faults, 1ull);
+                pg += kWaves;
+                continue;
+            }
+            const int second = head + 1 == S ? 0 : head + 1;
+            const bool pair = pg + kWaves < pg_end && ((real_mask >> second) & 1);
+            // the ring is full: S - 1 groups are newer than the head's, S - 2 newer than its successor's
+            wait_groups<FP8>(pair ? S - 2 : S - 1);
+            PageRegs pa;
             u32x4 ka[4];
-            float score_scale = p.scale_log2e, p_scale = 1.f;
-            if (FP8) {
-                u32x2 vraw[4], kraw[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    vraw[u] = *(const u32x2 *)(tile + geo::kTile + v_read + u * geo::kRow);
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    kraw[kk] = *(const u32x2 *)(tile + k_read[kk]);
-                score_scale *= *(const float *)(tile + 2 * geo::kTile);
-                p_scale = *(const float *)(tile + 2 * geo::kTile + geo::kScaleSlot);
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    pr.v[u] = fp8x8_to_bf16x8(vraw[u]);
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    ka[kk] = fp8x8_to_bf16x8(kraw[kk]);
+            float ks_a, vs_a;
+            read_stage<FP8>(ring + head * kStageBytes, k_read, v_read, pa, ka, ks_a, vs_a);
+            if (pair) {
+                PageRegs pb;
+                u32x4 kb[4];
+                float ks_b, vs_b;
+                read_stage<FP8>(ring + second * kStageBytes, k_read, v_read, pb, kb, ks_b, vs_b);
+                attend_pair(st, pa, pb, ka, kb, qb, p.scale_log2e * ks_a, p.scale_log2e * ks_b, vs_a, vs_b,
+                            (pg + kWaves) * kPageSize + 4 * j, C.t1, j);
+                real_mask &= ~((1 << head) | (1 << second));
+                head = second + 1 == S ? 0 : second + 1;
+                occ -= 2;
+                pg += 2 * kWaves;
             } else {
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    pr.v[u] = *(const u32x4 *)(tile + geo::kTile + v_read + u * geo::kRow);
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    ka[kk] = *(const u32x4 *)(tile + k_read[kk]);
-            }
-            attend_page(st, pr, ka, qb, score_scale, p_scale, pg * kPageSize + 4 * j, C.t1, j);
-            real_mask &= ~(1 << stage);
-            stage = stage + 1 == S ? 0 : stage + 1;
-            if (!looked) {
-                looked = true;
-                ADR_LOOK_AHEAD();
+                attend_page(st, pa, ka, qb, p.scale_log2e * ks_a, vs_a, pg * kPageSize + 4 * j, C.t1, j);
+                real_mask &= ~(1 << head);
+                head = second;
+                occ -= 1;
+                pg += kWaves;
             }
         }
-        if (!looked)
-            ADR_LOOK_AHEAD();
 
-        // ---- combine the four waves through the staging area of this item's parity
-        float l = st.l;
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        // Wave 0 needs the ticket it drew and the query tile it requested after the
-        // item's first page.  Each later page of the wave issued one more load
-        // group, so after S - 1 of them the ring's own wait count covers both;
-        // a shorter item waits for everything.
-        if (wave == 0) {
-            if (C.pg + (S - 1) * kWaves < C.pg_end)
-                wait_ring<FP8>(S);
-            else
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        }
-        float *so = staging + ((k & 1) * kWaves + wave) * (G * D); // [G][D]
-        if (j == 0 && r < G) {
-            sh.ml[k & 1][wave][r][0] = st.m;
-            sh.ml[k & 1][wave][r][1] = l;
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int g = 4 * j + i;
-            if (g < G) {
-                *(f32x4 *)(so + g * D + 8 * r) = f32x4{st.o[0][i], st.o[1][i], st.o[2][i], st.o[3][i]};
-                *(f32x4 *)(so + g * D + 8 * r + 4) = f32x4{st.o[4][i], st.o[5][i], st.o[6][i], st.o[7][i]};
-            }
-        }
-        if (tid == 0)
-            sh.slot[k & 1] = (int)next_ticket;
-        ring_barrier();
-        // Nothing written above is written again before the barrier of the item after
-        // the next one, which no wave reaches before all have finished reading here.
+        // ---- the look-ahead loads must have landed: they are older than the `age`
+        // newest groups, and no more than S groups are ever in flight
+        wait_groups<FP8>(min(age, S));
+        asm volatile("" : "+v"(next_ticket)::"memory"); // the ticket is read after the wait, not before
+        if (drawer)
+            publish(sh.rec[(k + 3) & (kQueue - 1)],
+                    decode_ticket(sh, sp, (int)__builtin_amdgcn_readfirstlane(next_ticket)), k + 3);
 
-        const float *sbase = staging + (k & 1) * kWaves * (G * D);
-        for (int idx = tid; idx < G * D; idx += kThreads) {
-            const int g = idx / D, dd = idx - g * D;
-            float M = sh.ml[k & 1][0][g][0];
-#pragma unroll
-            for (int w = 1; w < kWaves; ++w)
-                M = fmaxf(M, sh.ml[k & 1][w][g][0]);
-            float acc = 0.f, den = 0.f;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
-                const float f = fast_exp2(sh.ml[k & 1][w][g][0] - M);
-                acc += f * sbase[w * (G * D) + g * D + dd];
-                den += f * sh.ml[k & 1][w][g][1];
+        if (C.valid) {
+            // ---- deliver this wave's share; the last wave to arrive combines the four
+            const int buf = sp.nb == 2 ? (k & 1) : 0;
+            const int use = sp.nb == 2 ? (k >> 1) : k;
+            poll_equal(&sh.gen[buf], use, &sh.failed, sp.faults); // the buffer's previous item has been combined
+            float l = st.l;
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            float *so = staging + (buf * kWaves + wave) * (G * D); // [G][D]
+            if (j == 0 && r < G) {
+                sh.ml[buf][wave][r][0] = st.m;
+                sh.ml[buf][wave][r][1] = l;
             }
-            const float o = den > 0.f ? acc / den : 0.f;
-            const float lse = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
-            const int h = C.kvh * G + g;
-            if (C.n_parts == 1) {
-                const int64_t off = ((int64_t)C.b * p.Hq + h) * D + dd;
-                if (p.out_f32)
-                    ((float *)p.out)[off] = o;
-                else
-                    ((uint16_t *)p.out)[off] = (uint16_t)f32_to_bf16(o);
-                if (p.lse && dd == 0)
-                    p.lse[(int64_t)C.b * p.Hq + h] = lse;
-            } else {
-                const int64_t row = ((int64_t)C.b * p.max_parts + C.part) * p.Hq + h;
-                p.part_o[row * D + dd] = o;
-                if (dd == 0)
-                    p.part_lse[row] = lse;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int g = 4 * j + i;
+                if (g < G) {
+                    *(f32x4 *)(so + g * D + 8 * r) = f32x4{st.o[0][i], st.o[1][i], st.o[2][i], st.o[3][i]};
+                    *(f32x4 *)(so + g * D + 8 * r + 4) = f32x4{st.o[4][i], st.o[5][i], st.o[6][i], st.o[7][i]};
+                }
+            }
+            int arrived = 0;
+            lds_order();
+            if (lane == 0)
+                arrived = flag_add(&sh.arrive[buf], 1);
+            arrived = __builtin_amdgcn_readfirstlane(arrived);
+            lds_order();
+            if (arrived == kWaves - 1) {
+                const float *sbase = staging + buf * kWaves * (G * D);
+                for (int idx = lane; idx < G * (D / 4); idx += 64) {
+                    const int g = idx / (D / 4), c4 = (idx - g * (D / 4)) * 4;
+                    float mw[kWaves], M = kNegBig;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) {
+                        mw[w] = sh.ml[buf][w][g][0];
+                        M = fmaxf(M, mw[w]);
+                    }
+                    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                    float den = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) {
+                        const float f = fast_exp2(mw[w] - M);
+                        acc += f * *(const f32x4 *)(sbase + w * (G * D) + g * D + c4);
+                        den += f * sh.ml[buf][w][g][1];
+                    }
+                    const float inv = den > 0.f ? 1.f / den : 0.f;
+                    const f32x4 o = acc * inv;
+                    const float lse = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
+                    const int h = C.kvh * G + g;
+                    if (C.n_parts == 1) {
+                        const int64_t off = ((int64_t)C.b * p.Hq + h) * D + c4;
+                        if (p.out_f32) {
+                            *(f32x4 *)((float *)p.out + off) = o;
+                        } else {
+                            u32x2 packed;
+                            packed[0] = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
+                            packed[1] = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
+                            *(u32x2 *)((uint16_t *)p.out + off) = packed;
+                        }
+                        if (p.lse && c4 == 0)
+                            p.lse[(int64_t)C.b * p.Hq + h] = lse;
+                    } else {
+                        const int64_t row = ((int64_t)C.b * p.max_parts + C.part) * p.Hq + h;
+                        *(f32x4 *)(p.part_o + row * D + c4) = o;
+                        if (c4 == 0)
+                            p.part_lse[row] = lse;
+                    }
+                }
+                if (lane == 0) {
+                    flag_write(&sh.arrive[buf], 0);
+                    flag_write(&sh.gen[buf], use + 1);
+                }
+            }
+        } else {
+            // an item past the end still occupies its turn of the staging buffers
+            const int buf = sp.nb == 2 ? (k & 1) : 0;
+            const int use = sp.nb == 2 ? (k >> 1) : k;
+            poll_equal(&sh.gen[buf], use, &sh.failed, sp.faults);
+            int arrived = 0;
+            lds_order();
+            if (lane == 0)
+                arrived = flag_add(&sh.arrive[buf], 1);
+            arrived = __builtin_amdgcn_readfirstlane(arrived);
+            lds_order();
+            if (arrived == kWaves - 1 && lane == 0) {
+                flag_write(&sh.arrive[buf], 0);
+                flag_write(&sh.gen[buf], use + 1);
             }
         }
-        const int following = sh.slot[k & 1];
 
         // ---- next item becomes current
         C = N;
-        N = decode_ticket(sh, sp, following, wave);
+        N = fetch(sh.rec[(k + 2) & (kQueue - 1)], k + 2, &sh.failed, sp.faults);
         // The cursor is always inside the item that has just become current (issuing
         // the last page of an item moves it on, and so does an item without pages).
         ld_in_next = 0;
@@ -567,12 +820,14 @@ void decode_stream_kernel(const StreamParams sp)
             ADR_SETTLE(); // it had run out of pages there: move on into the new next item
     }
 
-#undef ADR_LOOK_AHEAD
 #undef ADR_ISSUE
 #undef ADR_SETTLE
+#undef ADR_FIRST_PAGE
+#undef ADR_END_PAGE
 
     // ---- hand the counters back to zero once every workgroup is through
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
     if (tid == 0) {
         const uint32_t done = atomicAdd(sp.ticket + 1, 1u);
         if (done == gridDim.x - 1) {
@@ -586,66 +841,98 @@ namespace {
 std::atomic<unsigned> g_next_slot{0};
 }
 
-constexpr bool kStreamKernelEnabled = true;
-
 bool decode_stream_supports(int d, int G, int B)
 {
-    return kStreamKernelEnabled && d == D && G >= 1 && G <= 16 && B <= kMaxStreamB;
+    return d == D && G >= 1 && G <= 16 && B <= kMaxStreamB;
 }
+
+namespace {
+struct DeviceInfo {
+    uint32_t *tickets = nullptr;
+    unsigned long long *faults = nullptr;
+    int workgroups = 0;
+};
+DeviceInfo g_info[64];
+std::atomic<int> g_ready[64];
+
+// per-device set-up, once: addresses of the counters, LDS limit, grid size
+hipError_t device_info(int *dev_out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= 64)
+        return hipErrorInvalidDevice;
+    *dev_out = dev;
+    if (g_ready[dev].load(std::memory_order_acquire))
+        return hipSuccess;
+    DeviceInfo di;
+    if ((e = hipGetSymbolAddress((void **)&di.tickets, HIP_SYMBOL(g_tickets))) != hipSuccess)
+        return e;
+    if ((e = hipGetSymbolAddress((void **)&di.faults, HIP_SYMBOL(g_stream_faults))) != hipSuccess)
+        return e;
+    if ((e = hipFuncSetAttribute((const void *)decode_stream_kernel<false>,
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes)) != hipSuccess)
+        return e;
+    if ((e = hipFuncSetAttribute((const void *)decode_stream_kernel<true>,
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes)) != hipSuccess)
+        return e;
+    int cus = 0;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess)
+        return e;
+    di.workgroups = cus; // one workgroup per compute unit: each takes most of its LDS
+    g_info[dev] = di;
+    g_ready[dev].store(1, std::memory_order_release);
+    return hipSuccess;
+}
+} // namespace
 
 hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStream_t stream)
 {
     if (!decode_stream_supports(d, p.G, p.B))
         return hipErrorInvalidValue;
-    // per-device set-up, once: address of the counter pool, LDS limit, grid size
-    struct DeviceInfo {
-        uint32_t *tickets = nullptr;
-        int workgroups = 0;
-    };
-    static DeviceInfo info[64];
-    static std::atomic<int> ready[64];
     int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess || dev < 0 || dev >= 64)
-        return hipErrorInvalidDevice;
-    // Ring depth: what one workgroup's LDS holds next to the staging area of the group size.
-    const size_t fixed = sizeof(Shared) + (size_t)2 * kWaves * p.G * D * sizeof(float);
+    hipError_t e = device_info(&dev);
+    if (e != hipSuccess)
+        return e;
+    // Ring depth: what one workgroup's LDS holds next to the query tiles and the
+    // staging buffers of the group size (one staging buffer only for the widest groups).
+    const int q_rows = (p.G + 3) / 4 * 4;
+    const int nb = p.G > 8 ? 1 : 2;
+    const size_t fixed = sizeof(Shared) + (size_t)kWaves * 2 * q_rows * (D * 2) +
+                         (size_t)nb * kWaves * p.G * D * sizeof(float);
     const int stage_bytes = fp8 ? Geo<true>::kStage : Geo<false>::kStage;
     int stages = (int)(((size_t)kMaxLdsBytes - fixed) / ((size_t)kWaves * stage_bytes));
     stages = std::min(stages, fp8 ? Geo<true>::kMaxStages : Geo<false>::kMaxStages);
     if (stages < 2)
         return hipErrorInvalidValue;
     const size_t lds = (size_t)kWaves * stages * stage_bytes + fixed;
-    if (!ready[dev].load(std::memory_order_acquire)) {
-        DeviceInfo di;
-        if ((e = hipGetSymbolAddress((void **)&di.tickets, HIP_SYMBOL(g_tickets))) != hipSuccess)
-            return e;
-        if ((e = hipFuncSetAttribute((const void *)decode_stream_kernel<false>,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes)) != hipSuccess)
-            return e;
-        if ((e = hipFuncSetAttribute((const void *)decode_stream_kernel<true>,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes)) != hipSuccess)
-            return e;
-        int cus = 0;
-        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess)
-            return e;
-        di.workgroups = cus; // one workgroup per compute unit: each takes most of its LDS
-        info[dev] = di;
-        ready[dev].store(1, std::memory_order_release);
-    }
     StreamParams sp;
     sp.d = p;
-    sp.ticket = info[dev].tickets + 2 * (g_next_slot.fetch_add(1) % kTicketSlots);
+    sp.ticket = g_info[dev].tickets + 2 * (g_next_slot.fetch_add(1) % kTicketSlots);
+    sp.faults = g_info[dev].faults;
     sp.pt = p.partition_tokens > 0 ? p.partition_tokens : (1 << 30);
     sp.stages = stages;
+    sp.nb = nb;
+    sp.q_rows = q_rows;
     int64_t grid = (int64_t)p.B * p.Hkv * p.max_parts;
-    if (grid > info[dev].workgroups)
-        grid = info[dev].workgroups;
+    if (grid > g_info[dev].workgroups)
+        grid = g_info[dev].workgroups;
     if (fp8)
         decode_stream_kernel<true><<<dim3((unsigned)grid), kThreads, lds, stream>>>(sp);
     else
         decode_stream_kernel<false><<<dim3((unsigned)grid), kThreads, lds, stream>>>(sp);
     return hipGetLastError();
+}
+
+// Number of bounded waits that expired in any launch on the current device since
+// the library was loaded (0 unless the kernel's hand-shakes are broken).  Synchronises.
+hipError_t read_stream_faults(unsigned long long *count)
+{
+    int dev = 0;
+    hipError_t e = device_info(&dev);
+    if (e != hipSuccess)
+        return e;
+    return hipMemcpy(count, g_info[dev].faults, sizeof(*count), hipMemcpyDeviceToHost);
 }
 
 } // namespace adr

@@ -283,3 +283,8 @@ def test_fp8_append_is_byte_exact_then_attend(d):
         ref, ref_lse, _ = oracle.decode_attention(W.bits(b.q), kh, vh, b.block_table, seq, b.wl.scale,
                                                   k_scale=ksh, v_scale=vsh)
         assert compare(out, lse, ref, ref_lse, what="fp8 append+attend %s" % kernel)[0] <= ATOL
+
+
+def test_resident_kernel_reports_no_expired_waits():
+    """Runs after the cases above: none of the waves' bounded waits may have expired."""
+    assert adr.adr_stream_fault_count() == 0

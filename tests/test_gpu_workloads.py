@@ -68,3 +68,8 @@ def test_workload_5_length_skew_sampled_rows():
     short_rows = np.nonzero(lens < 32768)[0]
     rows = np.concatenate([long_rows[:3], [long_rows[np.argmax(lens[long_rows])]], short_rows[:40]])
     run_workload(5, rows=np.unique(rows).astype(np.int32))
+
+
+def test_resident_kernel_reports_no_expired_waits():
+    """Runs after the cases above: none of the waves' bounded waits may have expired."""
+    assert adr.adr_stream_fault_count() == 0
