@@ -1,7 +1,8 @@
 // Persistent matrix-core decode attention (d = 128, bf16 or fp8-e4m3 cache, G <= 16,
 // B <= 512).
 //
-// The grid is one workgroup of four waves per compute unit.  The workgroups stay
+// The grid is one workgroup of four waves per compute unit (two for an fp8 cache
+// when they fit: see the launch function).  The workgroups stay
 // resident and pull work items from a ticket counter until none is left.  An
 // item is one (request, partition, kv-head); the four waves share it, wave w
 // taking pages w, w+4, ... of the partition.  Apart from that shared result the
@@ -92,7 +93,7 @@ struct Item {
     int n_parts; // partitions of the row (1: write the final result directly)
 };
 
-struct Rec {
+struct alignas(16) Rec {
     int seq; // index of the item this record describes; written last
     int valid, b, kvh, part, t1, n_parts, pad;
 };
@@ -209,12 +210,14 @@ __device__ __forceinline__ int flag_add(int *word, int value)
 // when it never does; the caller then goes on without what it waited for.
 __device__ __forceinline__ bool poll_equal(int *word, int want, int *failed, unsigned long long *faults)
 {
-    const int limit = __builtin_amdgcn_readfirstlane(flag_read(failed)) ? kSpinLimitAfterFault : kSpinLimit;
+    int limit = kSpinLimit;
     for (int spin = 0; spin < limit; ++spin) {
         if (__builtin_amdgcn_readfirstlane(flag_read(word)) == want) {
             lds_order();
             return true;
         }
+        if (spin == 0 && __builtin_amdgcn_readfirstlane(flag_read(failed)))
+            limit = kSpinLimitAfterFault;
         __builtin_amdgcn_s_sleep(1);
     }
     if ((threadIdx.x & 63) == 0) {
@@ -240,14 +243,29 @@ __device__ __forceinline__ void publish(Rec &rec, const Item &it, int seq)
 
 __device__ __forceinline__ Item fetch(Rec &rec, int seq, int *failed, unsigned long long *faults)
 {
+    // The record is 32 bytes; its stamp is written last, so a copy whose stamp is the
+    // wanted one is whole.  The common case is one round trip.
     Item it;
-    const bool ok = poll_equal(&rec.seq, seq, failed, faults);
-    it.valid = ok ? __builtin_amdgcn_readfirstlane(rec.valid) : 0;
-    it.b = __builtin_amdgcn_readfirstlane(rec.b);
-    it.kvh = __builtin_amdgcn_readfirstlane(rec.kvh);
-    it.part = __builtin_amdgcn_readfirstlane(rec.part);
-    it.t1 = __builtin_amdgcn_readfirstlane(rec.t1);
-    it.n_parts = __builtin_amdgcn_readfirstlane(rec.n_parts);
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    i32x4 lo, hi;
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(lo), "=&v"(hi)
+                 : "v"(lds_address(&rec))
+                 : "memory");
+    bool ok = __builtin_amdgcn_readfirstlane(lo[0]) == seq;
+    if (!ok) {
+        ok = poll_equal(&rec.seq, seq, failed, faults);
+        asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(lo), "=&v"(hi)
+                     : "v"(lds_address(&rec))
+                     : "memory");
+    }
+    it.valid = ok ? __builtin_amdgcn_readfirstlane(lo[1]) : 0;
+    it.b = __builtin_amdgcn_readfirstlane(lo[2]);
+    it.kvh = __builtin_amdgcn_readfirstlane(lo[3]);
+    it.part = __builtin_amdgcn_readfirstlane(hi[0]);
+    it.t1 = __builtin_amdgcn_readfirstlane(hi[1]);
+    it.n_parts = __builtin_amdgcn_readfirstlane(hi[2]);
     return it;
 }
 
@@ -688,6 +706,8 @@ void decode_stream_kernel(const StreamParams sp)
             const bool pair = pg + kWaves < pg_end && ((real_mask >> second) & 1);
             // the ring is full: S - 1 groups are newer than the head's, S - 2 newer than its successor's
             wait_groups<FP8>(pair ? S - 2 : S - 1);
+            // Copy the stage(s) to registers, hand the slots straight back to the ring and
+            // refill them, so that the loads are under way while this step computes.
             PageRegs pa;
             u32x4 ka[4];
             float ks_a, vs_a;
@@ -697,17 +717,23 @@ void decode_stream_kernel(const StreamParams sp)
                 u32x4 kb[4];
                 float ks_b, vs_b;
                 read_stage<FP8>(ring + second * kStageBytes, k_read, v_read, pb, kb, ks_b, vs_b);
-                attend_pair(st, pa, pb, ka, kb, qb, p.scale_log2e * ks_a, p.scale_log2e * ks_b, vs_a, vs_b,
-                            (pg + kWaves) * kPageSize + 4 * j, C.t1, j);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the copies are complete
                 real_mask &= ~((1 << head) | (1 << second));
                 head = second + 1 == S ? 0 : second + 1;
                 occ -= 2;
+                while (occ < S)
+                    ADR_ISSUE();
+                attend_pair(st, pa, pb, ka, kb, qb, p.scale_log2e * ks_a, p.scale_log2e * ks_b, vs_a, vs_b,
+                            (pg + kWaves) * kPageSize + 4 * j, C.t1, j);
                 pg += 2 * kWaves;
             } else {
-                attend_page(st, pa, ka, qb, p.scale_log2e * ks_a, vs_a, pg * kPageSize + 4 * j, C.t1, j);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 real_mask &= ~(1 << head);
                 head = second;
                 occ -= 1;
+                while (occ < S)
+                    ADR_ISSUE();
+                attend_page(st, pa, ka, qb, p.scale_log2e * ks_a, vs_a, pg * kPageSize + 4 * j, C.t1, j);
                 pg += kWaves;
             }
         }
@@ -879,7 +905,7 @@ hipError_t device_info(int *dev_out)
     int cus = 0;
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess)
         return e;
-    di.workgroups = cus; // one workgroup per compute unit: each takes most of its LDS
+    di.workgroups = cus; // compute units: a workgroup takes most, or half, of one's LDS
     g_info[dev] = di;
     g_ready[dev].store(1, std::memory_order_release);
     return hipSuccess;
@@ -896,12 +922,22 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
         return e;
     // Ring depth: what one workgroup's LDS holds next to the query tiles and the
     // staging buffers of the group size (one staging buffer only for the widest groups).
+    // An fp8 pass is bound by what one wave per SIMD can compute, not by memory, and
+    // its stages are half the size: where two workgroups fit in a compute unit's LDS
+    // with a ring of two stages each, run two (measured: 1.4x).
     const int q_rows = (p.G + 3) / 4 * 4;
     const int nb = p.G > 8 ? 1 : 2;
     const size_t fixed = sizeof(Shared) + (size_t)kWaves * 2 * q_rows * (D * 2) +
                          (size_t)nb * kWaves * p.G * D * sizeof(float);
     const int stage_bytes = fp8 ? Geo<true>::kStage : Geo<false>::kStage;
-    int stages = (int)(((size_t)kMaxLdsBytes - fixed) / ((size_t)kWaves * stage_bytes));
+    int per_cu = fp8 ? 2 : 1;
+    int stages = 0;
+    for (; per_cu >= 1; --per_cu) {
+        const size_t share = (size_t)kMaxLdsBytes / per_cu;
+        stages = share > fixed ? (int)((share - fixed) / ((size_t)kWaves * stage_bytes)) : 0;
+        if (stages >= 2)
+            break;
+    }
     stages = std::min(stages, fp8 ? Geo<true>::kMaxStages : Geo<false>::kMaxStages);
     if (stages < 2)
         return hipErrorInvalidValue;
@@ -915,8 +951,8 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
     sp.nb = nb;
     sp.q_rows = q_rows;
     int64_t grid = (int64_t)p.B * p.Hkv * p.max_parts;
-    if (grid > g_info[dev].workgroups)
-        grid = g_info[dev].workgroups;
+    if (grid > (int64_t)g_info[dev].workgroups * per_cu)
+        grid = (int64_t)g_info[dev].workgroups * per_cu;
     if (fp8)
         decode_stream_kernel<true><<<dim3((unsigned)grid), kThreads, lds, stream>>>(sp);
     else
