@@ -479,6 +479,15 @@ void decode_stream_kernel(const StreamParams sp)
     const int j = lane >> 4;
     const int B = p.B, Hkv = p.Hkv, G = p.G;
 
+    // The first three tickets: drawn before anything else, so that the round trip
+    // overlaps the scan below.
+    uint32_t first_ticket = 0;
+    if (tid == 0)
+        asm volatile("s_nop 4\n\tglobal_atomic_add %0, %1, %2, %3 sc0"
+                     : "=&v"(first_ticket)
+                     : "v"(0), "v"(3), "s"(sp.ticket)
+                     : "memory");
+
     // ---- partitions per row: exclusive prefix sums over the rows, four rows per thread
     {
         int f[4], g[4], sf = 0, sg = 0;
@@ -543,9 +552,10 @@ void decode_stream_kernel(const StreamParams sp)
             sh.pref_rag[B] = tg;
             sh.total[0] = tf;
             sh.total[1] = tg;
-            sh.first[0] = (int)atomicAdd(sp.ticket, 1u);
-            sh.first[1] = (int)atomicAdd(sp.ticket, 1u);
-            sh.first[2] = (int)atomicAdd(sp.ticket, 1u);
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(first_ticket)::"memory");
+            sh.first[0] = (int)first_ticket;
+            sh.first[1] = (int)first_ticket + 1;
+            sh.first[2] = (int)first_ticket + 2;
         }
         __syncthreads();
         if (wave < 3)
@@ -598,7 +608,6 @@ void decode_stream_kernel(const StreamParams sp)
     Item C = fetch(sh.rec[0], 0, &sh.failed, sp.faults);
     Item N = fetch(sh.rec[1], 1, &sh.failed, sp.faults);
     issue_query(myq, sp, C, q_lane);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- load cursor: the next page of this wave's stream to be issued.  It runs
     // through the current item and on into the next one, never further.  It keeps
@@ -649,6 +658,11 @@ void decode_stream_kernel(const StreamParams sp)
         ++age;                                                                                    \
     } while (0)
     ADR_SETTLE();
+    // Fill the ring behind the first item's query rows; once no more than the ring's
+    // loads are in flight, those rows have landed.
+    while (occ < S)
+        ADR_ISSUE();
+    wait_groups<FP8>(S);
 
     uint32_t next_ticket = 0;
     int invalid_run = 0;
