@@ -15,6 +15,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -90,6 +91,12 @@ def main():
     ap.add_argument("--cache-dtype", default="bf16", choices=["bf16", "fp8"],
                     help="fp8: caches quantised to e4m3 bytes with one fp32 scale per (page, kv-head)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--corun-gemm", action="store_true",
+                    help="colocation measurement: the attention steps on one stream while bf16 8192^3 matrix "
+                         "products run on another; prints its own JSON line (alone and contended rates)")
+    ap.add_argument("--cu-sweep", action="store_true",
+                    help="with --corun-gemm: repeat the measurement with the attention confined to 32, 64, ... "
+                         "compute units and the matrix products to the others")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch adr_probe_copy once on 1 GiB (calibrates profiler byte counters)")
     args = ap.parse_args()
@@ -141,6 +148,9 @@ def main():
                 adr.adr_decode_merge(out, seq, st["max_len"], part, ws)
                 e2.record()
                 events.append((e0, e1, e2))
+
+    if args.corun_gemm:
+        return corun_gemm(args, wl, st, one_step, bytes_per_token, layers, part)
 
     if args.probe_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
@@ -208,6 +218,177 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+def corun_gemm(args, wl, st, one_step, bytes_per_token, layers, part):
+    """Attention and a compute-bound neighbour sharing the GPU (the paper's colocation of the
+    attention executor with prefill, Sec. 3.3): stream A runs the K timed steps, stream B runs
+    bf16 8192 x 8192 x 8192 products back to back.  Each is timed alone and then together; the
+    contended figures count only work that overlapped the other stream's activity."""
+    K, Wm = args.steps, args.warmup
+    b = st["batch"]
+    dev = "cuda:0"
+    if args.cu_sweep:
+        return cu_sweep(args, wl, st, one_step, bytes_per_token, layers, part)
+    n = 8192
+    ga = W.randn_bf16((n, n), wl.seed + 50, dev)
+    gb = W.randn_bf16((n, n), wl.seed + 51, dev)
+    gc = torch.empty((n, n), dtype=torch.bfloat16, device=dev)
+    flop = 2.0 * n ** 3
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()      # default priority, both
+    tokens = [int(b.lens_before.sum()) + wl.B * (s + 1) for s in range(Wm, Wm + K)]
+    kv_bytes = layers * sum(tokens) * bytes_per_token
+
+    def attention_pass():
+        for s in range(Wm, Wm + K):
+            one_step(s)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    for _ in range(3):
+        torch.matmul(ga, gb, out=gc)
+    with torch.cuda.stream(sa):
+        for s in range(Wm):
+            one_step(s)
+    torch.cuda.synchronize()
+
+    # alone
+    a0, a1 = ev(), ev()
+    with torch.cuda.stream(sa):
+        a0.record(); attention_pass(); a1.record()
+    torch.cuda.synchronize()
+    attn_alone_ms = a0.elapsed_time(a1)
+    g0, g1 = ev(), ev()
+    n_alone = 20
+    with torch.cuda.stream(sb):
+        g0.record()
+        for _ in range(n_alone):
+            torch.matmul(ga, gb, out=gc)
+        g1.record()
+    torch.cuda.synchronize()
+    gemm_alone_ms = g0.elapsed_time(g1) / n_alone
+
+    # together: enough products to cover the attention pass even if it slows down threefold
+    n_gemm = max(4, int(math.ceil(3.0 * attn_alone_ms / gemm_alone_ms)) + 2)
+    marks = [ev() for _ in range(n_gemm + 1)]
+    c0, c1 = ev(), ev()
+    with torch.cuda.stream(sb):
+        marks[0].record()
+        for i in range(n_gemm):
+            torch.matmul(ga, gb, out=gc)
+            marks[i + 1].record()
+    with torch.cuda.stream(sa):
+        c0.record(); attention_pass(); c1.record()
+    torch.cuda.synchronize()
+    attn_co_ms = c0.elapsed_time(c1)
+    # products that started after the attention began and ended before it finished
+    inside = [marks[i].elapsed_time(marks[i + 1]) for i in range(n_gemm)
+              if c0.elapsed_time(marks[i]) >= 0 and marks[i + 1].elapsed_time(c1) >= 0]
+    gemm_co_ms = float(np.mean(inside)) if inside else float("nan")
+    line = {
+        "metric": "decode_attention_attended_kv_bandwidth_colocated", "unit": "GB/s",
+        "value": round(kv_bytes / attn_co_ms / 1e6, 1), "n_gpus": 1, "steps": K, "warmup": Wm,
+        "higher_is_better": True, "dtype": args.cache_dtype, "data": "synthetic",
+        "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d, %d layers, partition %d; neighbour: bf16 %d^3 "
+                               "torch.matmul on a second stream" % (wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, layers,
+                                                                   part, n)},
+        "attention_alone_GBps": round(kv_bytes / attn_alone_ms / 1e6, 1),
+        "attention_contended_GBps": round(kv_bytes / attn_co_ms / 1e6, 1),
+        "attention_ms_alone": round(attn_alone_ms, 4), "attention_ms_contended": round(attn_co_ms, 4),
+        "gemm_alone_TFLOPs": round(flop / gemm_alone_ms / 1e9, 1),
+        "gemm_contended_TFLOPs": round(flop / gemm_co_ms / 1e9, 1) if inside else None,
+        "gemm_ms_alone": round(gemm_alone_ms, 4), "gemm_ms_contended": round(gemm_co_ms, 4) if inside else None,
+        "gemms_inside_attention_window": len(inside),
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+def cu_sweep(args, wl, st, one_step, bytes_per_token, layers, part):
+    """Sec. 3.3's question on this chip: how much attention bandwidth does a fraction of the compute
+    units obtain, and what does the neighbour lose?  The attention runs on a stream whose queue is
+    masked to the first n compute-unit bits, the matrix products on a stream masked to the rest."""
+    K, Wm = args.steps, args.warmup
+    b = st["batch"]
+    dev = "cuda:0"
+    total_cus = torch.cuda.get_device_properties(0).multi_processor_count
+    n = 8192
+    ga = W.randn_bf16((n, n), wl.seed + 50, dev)
+    gb = W.randn_bf16((n, n), wl.seed + 51, dev)
+    gc = torch.empty((n, n), dtype=torch.bfloat16, device=dev)
+    flop = 2.0 * n ** 3
+    tokens = [int(b.lens_before.sum()) + wl.B * (s + 1) for s in range(Wm, Wm + K)]
+    kv_bytes = layers * sum(tokens) * bytes_per_token
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def attention_pass():
+        for s in range(Wm, Wm + K):
+            one_step(s)
+
+    for s in range(Wm):
+        one_step(s)
+    for _ in range(3):
+        torch.matmul(ga, gb, out=gc)
+    torch.cuda.synchronize()
+    rows = []
+    for n_attn in range(32, total_cus + 1, 32):
+        ha = adr.adr_stream_create_cu_mask([i < n_attn for i in range(total_cus)])
+        sa = torch.cuda.ExternalStream(ha)
+        row = {"attention_cus": n_attn, "gemm_cus": total_cus - n_attn}
+        a0, a1 = ev(), ev()
+        with torch.cuda.stream(sa):
+            attention_pass()                      # warm-up on this stream
+            a0.record(); attention_pass(); a1.record()
+        torch.cuda.synchronize()
+        alone_ms = a0.elapsed_time(a1)
+        row["attention_alone_GBps"] = round(kv_bytes / alone_ms / 1e6, 1)
+        if n_attn < total_cus:
+            hb = adr.adr_stream_create_cu_mask([i >= n_attn for i in range(total_cus)])
+            sb = torch.cuda.ExternalStream(hb)
+            g0, g1 = ev(), ev()
+            with torch.cuda.stream(sb):
+                torch.matmul(ga, gb, out=gc)
+                g0.record()
+                for _ in range(8):
+                    torch.matmul(ga, gb, out=gc)
+                g1.record()
+            torch.cuda.synchronize()
+            gemm_ms = g0.elapsed_time(g1) / 8
+            row["gemm_alone_TFLOPs"] = round(flop / gemm_ms / 1e9, 1)
+            n_gemm = max(4, int(math.ceil(2.0 * alone_ms / gemm_ms)) + 2)
+            marks = [ev() for _ in range(n_gemm + 1)]
+            c0, c1 = ev(), ev()
+            with torch.cuda.stream(sb):
+                marks[0].record()
+                for i in range(n_gemm):
+                    torch.matmul(ga, gb, out=gc)
+                    marks[i + 1].record()
+            with torch.cuda.stream(sa):
+                c0.record(); attention_pass(); c1.record()
+            torch.cuda.synchronize()
+            co_ms = c0.elapsed_time(c1)
+            inside = [marks[i].elapsed_time(marks[i + 1]) for i in range(n_gemm)
+                      if c0.elapsed_time(marks[i]) >= 0 and marks[i + 1].elapsed_time(c1) >= 0]
+            row["attention_contended_GBps"] = round(kv_bytes / co_ms / 1e6, 1)
+            row["gemm_contended_TFLOPs"] = round(flop / float(np.mean(inside)) / 1e9, 1) if inside else None
+            row["gemms_inside_attention_window"] = len(inside)
+            del sb
+            adr.adr_stream_destroy(hb)
+        del sa
+        adr.adr_stream_destroy(ha)
+        log("cu sweep: %s" % json.dumps(row))
+        rows.append(row)
+    line = {"metric": "decode_attention_bandwidth_vs_compute_units", "unit": "GB/s", "n_gpus": 1, "steps": K,
+            "warmup": Wm, "dtype": args.cache_dtype, "data": "synthetic",
+            "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d, %d layers, partition %d; neighbour: bf16 %d^3 "
+                                   "torch.matmul on the complementary compute units" % (
+                                       wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, layers, part, n)},
+            "total_cus": total_cus, "rows": rows}
     print(json.dumps(line), flush=True)
     return 0
 

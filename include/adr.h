@@ -181,6 +181,21 @@ int adr_probe_stream_read(const void *src, size_t bytes, void *sink, void *strea
 int adr_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /*
+ * Streams confined to a subset of the compute units (Sec. 3.3: the executor and
+ * the prefill engine share one GPU, each on a fraction of its cores; the paper
+ * sets the split with MPS, here it is a queue's compute-unit mask).
+ * adr_stream_create_cu_mask returns in *stream (a HOST pointer to a void*) a new
+ * hipStream_t of default priority whose kernels run only on the compute units
+ * whose bit is set in cu_mask (HOST pointer, n_words 32-bit words, bit i of word
+ * w = unit 32*w + i); pass it as `stream` to the calls above, or wrap it for
+ * other libraries.  adr_stream_destroy releases it after its work has finished.
+ * Errors: ADR_ERR_NULL, ADR_ERR_SHAPE (n_words <= 0 or an empty mask),
+ * ADR_ERR_LAUNCH (the runtime refused).
+ */
+int adr_stream_create_cu_mask(void **stream, const uint32_t *cu_mask, int n_words);
+int adr_stream_destroy(void *stream);
+
+/*
  * Self-check of the resident-workgroup kernel (ADR_KERNEL_MFMA): its waves hand
  * work to each other through flags in on-chip memory, and every wait on such a
  * flag is bounded.  `*count` (a HOST pointer) receives the number of waits that

@@ -17,7 +17,8 @@ PARTIALS_ONLY = 16
 
 EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention",
            "adr_decode_merge", "adr_lse_merge", "adr_probe_stream_read", "adr_probe_copy",
-           "adr_stream_fault_count", "adr_status_string", "adr_version")
+           "adr_stream_create_cu_mask", "adr_stream_destroy", "adr_stream_fault_count",
+           "adr_status_string", "adr_version")
 
 
 class AdrError(RuntimeError):
@@ -67,6 +68,10 @@ def load_library():
     lib.adr_probe_stream_read.argtypes = [vp, sz, vp, vp]
     lib.adr_probe_copy.restype = i32
     lib.adr_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.adr_stream_create_cu_mask.restype = i32
+    lib.adr_stream_create_cu_mask.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_uint32), i32]
+    lib.adr_stream_destroy.restype = i32
+    lib.adr_stream_destroy.argtypes = [vp]
     lib.adr_stream_fault_count.restype = i32
     lib.adr_stream_fault_count.argtypes = [ctypes.POINTER(ctypes.c_uint64)]
     lib.adr_status_string.restype = ctypes.c_char_p
@@ -75,6 +80,24 @@ def load_library():
     lib.adr_version.argtypes = []
     _lib = lib
     return lib
+
+
+def adr_stream_create_cu_mask(cu_bits) -> int:
+    """A stream whose kernels run only on the compute units i with cu_bits[i] true; returns the
+    raw hipStream_t handle (wrap it with torch.cuda.ExternalStream to use it from torch)."""
+    bits = [bool(x) for x in cu_bits]
+    words = (ctypes.c_uint32 * ((len(bits) + 31) // 32))()
+    for i, on in enumerate(bits):
+        if on:
+            words[i // 32] |= 1 << (i % 32)
+    handle = ctypes.c_void_p()
+    _check(load_library().adr_stream_create_cu_mask(ctypes.byref(handle), words, len(words)),
+           "adr_stream_create_cu_mask")
+    return int(handle.value)
+
+
+def adr_stream_destroy(handle: int) -> None:
+    _check(load_library().adr_stream_destroy(ctypes.c_void_p(handle)), "adr_stream_destroy")
 
 
 def adr_stream_fault_count() -> int:

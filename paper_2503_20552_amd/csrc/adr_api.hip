@@ -54,6 +54,31 @@ extern "C" {
 
 int adr_version(void) { return 100; }
 
+int adr_stream_create_cu_mask(void **stream, const uint32_t *cu_mask, int n_words)
+{
+    if (!stream || !cu_mask)
+        return ADR_ERR_NULL;
+    if (n_words <= 0)
+        return ADR_ERR_SHAPE;
+    uint32_t any = 0;
+    for (int i = 0; i < n_words; ++i)
+        any |= cu_mask[i];
+    if (!any)
+        return ADR_ERR_SHAPE;
+    hipStream_t s = nullptr;
+    if (hipExtStreamCreateWithCUMask(&s, (uint32_t)n_words, cu_mask) != hipSuccess)
+        return ADR_ERR_LAUNCH;
+    *stream = (void *)s;
+    return ADR_OK;
+}
+
+int adr_stream_destroy(void *stream)
+{
+    if (!stream)
+        return ADR_ERR_NULL;
+    return hipStreamDestroy((hipStream_t)stream) == hipSuccess ? ADR_OK : ADR_ERR_LAUNCH;
+}
+
 int adr_stream_fault_count(uint64_t *count)
 {
     if (!count)

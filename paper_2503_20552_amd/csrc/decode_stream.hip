@@ -289,36 +289,30 @@ __device__ __forceinline__ void issue_query(char *qtile, const StreamParams &sp,
     asm volatile("" ::: "memory");
 }
 
-// The direct-to-LDS loads of one page for one kv-head into ring stage `tile`:
-// K rows (swizzled), V rows (natural) and, for an fp8 cache, the page's two
-// scales (lane 0 only: the other lanes' offsets are out of the descriptor's range).
-template <bool FP8>
-__device__ __forceinline__ void issue_page(char *tile, __amdgpu_buffer_rsrc_t krsrc,
-                                           __amdgpu_buffer_rsrc_t vrsrc, __amdgpu_buffer_rsrc_t ksrsrc,
-                                           __amdgpu_buffer_rsrc_t vsrsrc, const uint32_t (&k_lane)[4],
-                                           const uint32_t (&v_lane)[4], uint32_t s_lane,
-                                           uint32_t head_bytes, uint32_t scale_bytes)
+// Half of the direct-to-LDS loads of one page for one kv-head into ring stage
+// `tile`: WHICH = 0 the K rows (swizzled), WHICH = 1 the V rows (natural), each
+// followed, for an fp8 cache, by the page's scale of that tensor (lane 0 only: the
+// other lanes' offsets are out of the descriptor's range).  The two halves of a
+// page are issued separately so that a step's loads can be spread between its
+// arithmetic: a wave that issues sixteen of them back to back sits in the queue
+// of the compute unit's one load unit behind the other waves' loads.
+template <bool FP8, int WHICH>
+__device__ __forceinline__ void issue_half(char *tile, __amdgpu_buffer_rsrc_t rsrc,
+                                           __amdgpu_buffer_rsrc_t scale_rsrc, const uint32_t (&lane_off)[4],
+                                           uint32_t s_lane, uint32_t head_bytes, uint32_t scale_bytes)
 {
     typedef Geo<FP8> geo;
     asm volatile("" ::: "memory");
 #pragma unroll
     for (int i = 0; i < geo::kTileLoads; ++i)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            krsrc, (__attribute__((address_space(3))) void *)(tile + i * 1024), 16, k_lane[i],
-            head_bytes, 0, kStreamOnce);
-#pragma unroll
-    for (int i = 0; i < geo::kTileLoads; ++i)
+            rsrc, (__attribute__((address_space(3))) void *)(tile + WHICH * geo::kTile + i * 1024), 16,
+            lane_off[i], head_bytes, 0, kStreamOnce);
+    if (FP8)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            vrsrc, (__attribute__((address_space(3))) void *)(tile + geo::kTile + i * 1024), 16,
-            v_lane[i], head_bytes, 0, kStreamOnce);
-    if (FP8) {
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            ksrsrc, (__attribute__((address_space(3))) void *)(tile + 2 * geo::kTile), 4, s_lane,
-            scale_bytes, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            vsrsrc, (__attribute__((address_space(3))) void *)(tile + 2 * geo::kTile + geo::kScaleSlot),
-            4, s_lane, scale_bytes, 0, 0);
-    }
+            scale_rsrc,
+            (__attribute__((address_space(3))) void *)(tile + 2 * geo::kTile + WHICH * geo::kScaleSlot), 4,
+            s_lane, scale_bytes, 0, 0);
     asm volatile("" ::: "memory");
 }
 
@@ -344,16 +338,20 @@ __device__ __forceinline__ void wait_groups(int groups)
 #undef ADR_WAIT_CASE
 }
 
-// Two pages at once (page A = tokens tok .. , page B = the wave's next page, 64
-// tokens further on): S = K Q^T for both, one online-softmax step over the 32
-// tokens, O += P V with the contraction running over both pages.  Only B can be
-// the partition's last, partly filled page.
-__device__ __forceinline__ void attend_pair(WaveState &st, PageRegs &pa, PageRegs &pb,
-                                            const u32x4 (&ka)[4], const u32x4 (&kb)[4],
-                                            const u32x4 (&qb)[4], float score_a, float score_b,
-                                            float p_scale_a, float p_scale_b, int tok_b, int t1, int j)
+// Two pages at once (page A, and page B = the wave's next page, 64 tokens further
+// on): S = K Q^T for both, one online-softmax step over the 32 tokens, O += P V
+// with the contraction running over both pages.  Only B can be the partition's
+// last, partly filled page.  The work comes in four pieces so that the caller can
+// issue loads between them.
+struct PairWeights {
+    u32x4 ah, al; // eight bf16 each: elements 0..3 <-> page A tokens 4j+i, 4..7 <-> page B tokens 4j+i
+};
+
+__device__ __forceinline__ void pair_scores(f32x4 &sa, f32x4 &sb, const u32x4 (&ka)[4],
+                                            const u32x4 (&kb)[4], const u32x4 (&qb)[4])
 {
-    f32x4 sa = f32x4{0.f, 0.f, 0.f, 0.f}, sb = f32x4{0.f, 0.f, 0.f, 0.f};
+    sa = f32x4{0.f, 0.f, 0.f, 0.f};
+    sb = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
         sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kk]),
@@ -361,6 +359,12 @@ __device__ __forceinline__ void attend_pair(WaveState &st, PageRegs &pa, PageReg
         sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[kk]),
                                                      __builtin_bit_cast(bf16x8, qb[kk]), sb, 0, 0, 0);
     }
+}
+
+__device__ __forceinline__ PairWeights pair_softmax(WaveState &st, PageRegs &pb, f32x4 sa, f32x4 sb,
+                                                    float score_a, float score_b, float p_scale_a,
+                                                    float p_scale_b, int tok_b, int t1, int j)
+{
     // tok_b = index of the first of this lane's four tokens in page B
     const bool tail = tok_b - 4 * j + kPageSize > t1;
     float sc[8];
@@ -404,14 +408,21 @@ __device__ __forceinline__ void attend_pair(WaveState &st, PageRegs &pa, PageReg
         ph[i] = __float_as_uint(pw) & 0xffff0000u;            // bf16 head (truncated)
         pl[i] = __float_as_uint(pw - __uint_as_float(ph[i])); // remainder, exact in fp32
     }
-    u32x4 ah, al; // eight bf16 each: elements 0..3 <-> page A tokens 4j+i, 4..7 <-> page B tokens 4j+i
+    PairWeights w;
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-        ah[h] = (ph[2 * h] >> 16) | ph[2 * h + 1];
-        al[h] = (pl[2 * h] >> 16) | (pl[2 * h + 1] & 0xffff0000u);
+        w.ah[h] = (ph[2 * h] >> 16) | ph[2 * h + 1];
+        w.al[h] = (pl[2 * h] >> 16) | (pl[2 * h + 1] & 0xffff0000u);
     }
+    return w;
+}
+
+template <int E0, int E1>
+__device__ __forceinline__ void pair_pv(WaveState &st, const PairWeights &w, const PageRegs &pa,
+                                        const PageRegs &pb)
+{
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
+    for (int e = E0; e < E1; ++e) {
         const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
         u32x4 vb;
         vb[0] = __builtin_amdgcn_perm(pa.v[1][e >> 1], pa.v[0][e >> 1], sel);
@@ -419,9 +430,9 @@ __device__ __forceinline__ void attend_pair(WaveState &st, PageRegs &pa, PageReg
         vb[2] = __builtin_amdgcn_perm(pb.v[1][e >> 1], pb.v[0][e >> 1], sel);
         vb[3] = __builtin_amdgcn_perm(pb.v[3][e >> 1], pb.v[2][e >> 1], sel);
         st.o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-            __builtin_bit_cast(bf16x8, ah), __builtin_bit_cast(bf16x8, vb), st.o[e], 0, 0, 0);
+            __builtin_bit_cast(bf16x8, w.ah), __builtin_bit_cast(bf16x8, vb), st.o[e], 0, 0, 0);
         st.o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-            __builtin_bit_cast(bf16x8, al), __builtin_bit_cast(bf16x8, vb), st.o[e], 0, 0, 0);
+            __builtin_bit_cast(bf16x8, w.al), __builtin_bit_cast(bf16x8, vb), st.o[e], 0, 0, 0);
     }
 }
 
@@ -638,24 +649,44 @@ void decode_stream_kernel(const StreamParams sp)
     // next load group goes to `tail`.  real_mask marks the slots that hold a page.
     int head = 0, tail = 0, occ = 0, real_mask = 0;
     int age = 0; // page-load groups issued since this item's look-ahead loads
-#define ADR_ISSUE()                                                                               \
-    do { /* fill the ring's tail slot with the cursor's page, or with a group of null loads */    \
-        char *tile_ = ring + tail * kStageBytes;                                                  \
+    // A page is issued in two halves (K, then V); the second half takes the page
+    // from the pend_* copies, because the cursor has moved on by then.
+    char *pend_tile = ring;
+    int pend_ok = 0, pend_id = 0;
+    uint32_t pend_head = 0, pend_scale = 0;
+#define ADR_ISSUE_K()                                                                             \
+    do { /* the ring's tail slot takes the cursor's page, or a group of null loads: K half */     \
+        pend_tile = ring + tail * kStageBytes;                                                    \
+        pend_ok = ld_ok;                                                                          \
         if (ld_ok) {                                                                              \
-            issue_page<FP8>(tile_, page_rsrc(kc, ld_id, page_bytes),                              \
-                            page_rsrc(vc, ld_id, page_bytes), ks_rsrc, vs_rsrc, k_lane, v_lane,   \
-                            s_lane, ld_head, (uint32_t)(ld_id * Hkv + ld_kvh) * 4u);              \
+            pend_id = ld_id;                                                                      \
+            pend_head = ld_head;                                                                  \
+            pend_scale = (uint32_t)(ld_id * Hkv + ld_kvh) * 4u;                                   \
+            issue_half<FP8, 0>(pend_tile, page_rsrc(kc, ld_id, page_bytes), ks_rsrc, k_lane,      \
+                               s_lane, pend_head, pend_scale);                                    \
             real_mask |= 1 << tail;                                                               \
             ld_pg += kWaves;                                                                      \
             ADR_SETTLE();                                                                         \
         } else {                                                                                  \
-            issue_page<FP8>(tile_, null_rsrc, null_rsrc, null_rsrc, null_rsrc, k_lane, v_lane,    \
-                            s_lane, 0, 0);                                                        \
+            issue_half<FP8, 0>(pend_tile, null_rsrc, null_rsrc, k_lane, s_lane, 0, 0);            \
             real_mask &= ~(1 << tail);                                                            \
         }                                                                                         \
         tail = tail + 1 == S ? 0 : tail + 1;                                                      \
         ++occ;                                                                                    \
         ++age;                                                                                    \
+    } while (0)
+#define ADR_ISSUE_V()                                                                             \
+    do { /* V half of the page whose K half was issued last */                                    \
+        if (pend_ok)                                                                              \
+            issue_half<FP8, 1>(pend_tile, page_rsrc(vc, pend_id, page_bytes), vs_rsrc, v_lane,    \
+                               s_lane, pend_head, pend_scale);                                    \
+        else                                                                                      \
+            issue_half<FP8, 1>(pend_tile, null_rsrc, null_rsrc, v_lane, s_lane, 0, 0);            \
+    } while (0)
+#define ADR_ISSUE()                                                                               \
+    do {                                                                                          \
+        ADR_ISSUE_K();                                                                            \
+        ADR_ISSUE_V();                                                                            \
     } while (0)
     ADR_SETTLE();
     // Fill the ring behind the first item's query rows; once no more than the ring's
@@ -735,10 +766,17 @@ void decode_stream_kernel(const StreamParams sp)
                 real_mask &= ~((1 << head) | (1 << second));
                 head = second + 1 == S ? 0 : second + 1;
                 occ -= 2;
-                while (occ < S)
-                    ADR_ISSUE();
-                attend_pair(st, pa, pb, ka, kb, qb, p.scale_log2e * ks_a, p.scale_log2e * ks_b, vs_a, vs_b,
-                            (pg + kWaves) * kPageSize + 4 * j, C.t1, j);
+                // the two freed slots are refilled in four pieces between the pieces of the arithmetic
+                f32x4 sa, sb;
+                ADR_ISSUE_K();
+                pair_scores(sa, sb, ka, kb, qb);
+                ADR_ISSUE_V();
+                const PairWeights w = pair_softmax(st, pb, sa, sb, p.scale_log2e * ks_a, p.scale_log2e * ks_b,
+                                                   vs_a, vs_b, (pg + kWaves) * kPageSize + 4 * j, C.t1, j);
+                ADR_ISSUE_K();
+                pair_pv<0, 4>(st, w, pa, pb);
+                ADR_ISSUE_V();
+                pair_pv<4, 8>(st, w, pa, pb);
                 pg += 2 * kWaves;
             } else {
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -861,6 +899,8 @@ void decode_stream_kernel(const StreamParams sp)
     }
 
 #undef ADR_ISSUE
+#undef ADR_ISSUE_V
+#undef ADR_ISSUE_K
 #undef ADR_SETTLE
 #undef ADR_FIRST_PAGE
 #undef ADR_END_PAGE
@@ -964,9 +1004,23 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
     sp.stages = stages;
     sp.nb = nb;
     sp.q_rows = q_rows;
+    // A stream may be confined to some of the compute units: size the grid for those.
+    int cus = g_info[dev].workgroups;
+    {
+        uint32_t mask[32] = {0};
+        if (hipExtStreamGetCUMask(stream, 32, mask) == hipSuccess) {
+            int bits = 0;
+            for (uint32_t w : mask)
+                bits += __builtin_popcount(w);
+            if (bits > 0 && bits < cus)
+                cus = bits;
+        } else {
+            (void)hipGetLastError(); // not an error of this call's work
+        }
+    }
     int64_t grid = (int64_t)p.B * p.Hkv * p.max_parts;
-    if (grid > (int64_t)g_info[dev].workgroups * per_cu)
-        grid = (int64_t)g_info[dev].workgroups * per_cu;
+    if (grid > (int64_t)cus * per_cu)
+        grid = (int64_t)cus * per_cu;
     if (fp8)
         decode_stream_kernel<true><<<dim3((unsigned)grid), kThreads, lds, stream>>>(sp);
     else

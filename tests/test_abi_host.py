@@ -128,3 +128,17 @@ def test_workspace_size_formula():
     assert adr.adr_decode_workspace_bytes(4, 8, 128, 1000, 512) == rows * 128 * 4 + 256
     assert adr.adr_decode_workspace_bytes(4, 8, 128, 1024, 512) == rows * 128 * 4 + 256
     assert adr.adr_decode_workspace_bytes(4, 8, 128, 1025, 512) > rows * 128 * 4 + 256
+
+
+def test_cu_mask_stream_and_fault_count_reject_bad_arguments():
+    lib = adr.load_library()
+    handle = ctypes.c_void_p()
+    one = (ctypes.c_uint32 * 1)(1)
+    zero = (ctypes.c_uint32 * 2)(0, 0)
+    assert lib.adr_stream_create_cu_mask(None, one, 1) == NULL
+    assert lib.adr_stream_create_cu_mask(ctypes.byref(handle), None, 1) == NULL
+    assert lib.adr_stream_create_cu_mask(ctypes.byref(handle), one, 0) == SHAPE
+    assert lib.adr_stream_create_cu_mask(ctypes.byref(handle), zero, 2) == SHAPE
+    assert handle.value is None
+    assert lib.adr_stream_destroy(None) == NULL
+    assert lib.adr_stream_fault_count(None) == NULL
