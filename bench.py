@@ -94,6 +94,10 @@ def main():
     ap.add_argument("--corun-gemm", action="store_true",
                     help="colocation measurement: the attention steps on one stream while bf16 8192^3 matrix "
                          "products run on another; prints its own JSON line (alone and contended rates)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (all layers: append, attention, merge) into a HIP graph and replay "
+                         "it; prints its own JSON line with eager and replayed times and the CPU time spent "
+                         "enqueueing a step either way")
     ap.add_argument("--cu-sweep", action="store_true",
                     help="with --corun-gemm: repeat the measurement with the attention confined to 32, 64, ... "
                          "compute units and the matrix products to the others")
@@ -132,8 +136,9 @@ def main():
     # K and V of one token in one layer (+ an fp8 page's two scales per kv-head, shared by its 16 tokens)
     bytes_per_token = 2 * wl.Hkv * wl.d * elem + (2 * wl.Hkv * 4 / wl.page_size if fp8 else 0)
 
-    def one_step(s, events=None):
-        pos, seq = st["positions"][s], st["seq_lens"][s]
+    def one_step(s, events=None, pos=None, seq=None):
+        if pos is None:
+            pos, seq = st["positions"][s], st["seq_lens"][s]
         for li, cache in enumerate(st["caches"]):
             adr.adr_kv_append(cache, st["k_new"], st["v_new"], st["table"], pos)
             if events is None:
@@ -151,6 +156,8 @@ def main():
 
     if args.corun_gemm:
         return corun_gemm(args, wl, st, one_step, bytes_per_token, layers, part)
+    if args.graph:
+        return graph_replay(args, wl, st, one_step, out, bytes_per_token, layers, part)
 
     if args.probe_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
@@ -305,6 +312,71 @@ def corun_gemm(args, wl, st, one_step, bytes_per_token, layers, part):
     }
     print(json.dumps(line), flush=True)
     return 0
+
+
+def graph_replay(args, wl, st, one_step, out, bytes_per_token, layers, part):
+    """Sec. 3.2.2: the executor's per-layer kernels are launched from a pre-recorded graph, because
+    launching them one by one costs more CPU time than the kernels take on the GPU.  One step (every
+    layer's append, attention and merge) is recorded once, with the per-step inputs (positions,
+    lengths) in fixed device buffers that are overwritten before each replay."""
+    K, Wm = args.steps, args.warmup
+    b = st["batch"]
+    pos_buf = st["positions"][0].clone()
+    seq_buf = st["seq_lens"][0].clone()
+    tokens = [int(b.lens_before.sum()) + wl.B * (s + 1) for s in range(Wm, Wm + K)]
+    kv_bytes = layers * sum(tokens) * bytes_per_token
+
+    def timed(run_step):
+        torch.cuda.synchronize()
+        cpu = 0.0
+        t0 = time.perf_counter()
+        for s in range(Wm, Wm + K):
+            c0 = time.perf_counter()
+            run_step(s)
+            cpu += time.perf_counter() - c0
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / K * 1e3, cpu / K * 1e3
+
+    for s in range(Wm):
+        one_step(s)
+    eager_ms, eager_cpu_ms = timed(lambda s: one_step(s))
+    eager_out = out.clone()
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        one_step(0, pos=pos_buf, seq=seq_buf)             # warm the stream before recording
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        one_step(0, pos=pos_buf, seq=seq_buf)
+
+    def replay(s):
+        pos_buf.copy_(st["positions"][s])
+        seq_buf.copy_(st["seq_lens"][s])
+        graph.replay()
+
+    # the caches now hold the tokens of the eager pass at these positions already: the replays
+    # rewrite the same bytes, so the last step's output must equal the eager one bit for bit
+    graph_ms, graph_cpu_ms = timed(replay)
+    same = bool(torch.equal(out, eager_out))
+    n_launch = layers * 3
+    line = {
+        "metric": "decode_attention_attended_kv_bandwidth_graph_replay", "unit": "GB/s",
+        "value": round(kv_bytes / (graph_ms * K) / 1e6, 1), "n_gpus": 1, "steps": K, "warmup": Wm,
+        "higher_is_better": True, "dtype": args.cache_dtype, "data": "synthetic",
+        "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d, %d layers, partition %d; one HIP graph of %d kernel "
+                               "launches per step" % (wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, layers, part, n_launch)},
+        "eager_GBps": round(kv_bytes / (eager_ms * K) / 1e6, 1),
+        "eager_ms_per_step": round(eager_ms, 4), "graph_ms_per_step": round(graph_ms, 4),
+        "cpu_enqueue_ms_per_step_eager": round(eager_cpu_ms, 4),
+        "cpu_enqueue_ms_per_step_graph": round(graph_cpu_ms, 4),
+        "cpu_enqueue_us_per_layer_eager": round(eager_cpu_ms / layers * 1e3, 2),
+        "cpu_enqueue_us_per_layer_graph": round(graph_cpu_ms / layers * 1e3, 2),
+        "gpu_us_per_layer_graph": round(graph_ms / layers * 1e3, 2),
+        "replayed_output_equals_eager": same,
+    }
+    print(json.dumps(line), flush=True)
+    return 0 if same else 1
 
 
 def cu_sweep(args, wl, st, one_step, bytes_per_token, layers, part):

@@ -1005,8 +1005,12 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
     sp.nb = nb;
     sp.q_rows = q_rows;
     // A stream may be confined to some of the compute units: size the grid for those.
+    // (Not asked of a stream that is recording a graph: queries can end a capture.)
     int cus = g_info[dev].workgroups;
-    {
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capturing) != hipSuccess)
+        (void)hipGetLastError();
+    if (capturing == hipStreamCaptureStatusNone) {
         uint32_t mask[32] = {0};
         if (hipExtStreamGetCUMask(stream, 32, mask) == hipSuccess) {
             int bits = 0;

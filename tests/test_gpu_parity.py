@@ -285,6 +285,57 @@ def test_fp8_append_is_byte_exact_then_attend(d):
         assert compare(out, lse, ref, ref_lse, what="fp8 append+attend %s" % kernel)[0] <= ATOL
 
 
+def test_graph_replay_matches_eager_on_every_replay():
+    """Append + attention + merge of three layers recorded into one HIP graph; the per-step inputs
+    live in fixed buffers.  Each replay is checked against the same step run eagerly, with eager
+    work and synchronisation between the replays."""
+    n_steps, n_layers, part = 4, 3, 512
+    lens = np.asarray([700, 33, 1200, 5, 0, 511], dtype=np.int32)
+    wl = W.Workload(99, "case", B=len(lens), Hq=8, Hkv=2, d=128, lengths="given")
+    b = W.make_batch(wl, device="cpu", headroom_tokens=n_steps, seed_offset=70, lens_before=lens)
+    table = dev(b.block_table)
+    q = dev(b.q)
+    k_new, v_new = dev(b.k_new), dev(b.v_new)
+    lens0 = b.lens_before.copy()
+    max_len = int(lens0.max()) + n_steps
+    def fresh():
+        return [adr.KVCache(dev(b.k_cache), dev(b.v_cache)) for _ in range(n_layers)]
+    ws = torch.empty(max(adr.adr_decode_workspace_bytes(len(lens0), 8, 128, max_len, part), 256),
+                     dtype=torch.uint8, device="cuda:0")
+    out = torch.zeros((len(lens0), 8, 128), dtype=torch.float32, device="cuda:0")
+    pos_buf = dev(lens0.astype(np.int32))
+    seq_buf = dev((lens0 + 1).astype(np.int32))
+
+    def step(caches):
+        for c in caches:
+            adr.adr_kv_append(c, k_new, v_new, table, pos_buf)
+            adr.adr_decode_attention(out, q, c, table, seq_buf, b.wl.scale, max_len, part, ws, None,
+                                     adr.KERNEL_MFMA)
+
+    say("graph capture and replay")
+    eager_caches, graph_caches = fresh(), fresh()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step(fresh())                        # warm the stream and the library before recording
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(graph_caches)
+    for s in range(n_steps):
+        pos_buf.copy_(dev((lens0 + s).astype(np.int32)))
+        seq_buf.copy_(dev((lens0 + s + 1).astype(np.int32)))
+        step(eager_caches)
+        torch.cuda.synchronize()
+        want = out.clone()
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), "replay %d differs from the eager step" % s
+        for ce, cg in zip(eager_caches, graph_caches):
+            assert torch.equal(ce.k.view(torch.int16), cg.k.view(torch.int16))
+    assert adr.adr_stream_fault_count() == 0
+
+
 def test_resident_kernel_reports_no_expired_waits():
     """Runs after the cases above: none of the waves' bounded waits may have expired."""
     assert adr.adr_stream_fault_count() == 0
