@@ -101,6 +101,32 @@ __device__ __forceinline__ float group_sum(float x)
     return x;
 }
 
+// Reductions over the four lanes l, l^16, l^32, l^48 (the four 16-lane rows of a wave) with the
+// row-swap instructions of gfx950: v_permlane16_swap exchanges the odd rows of its first operand
+// with the even rows of its second, v_permlane32_swap the upper half of the first with the lower
+// half of the second.  Fed the same value twice, the two results hold, in every lane, the lane's
+// own value and its partner's (in one order or the other), so a commutative operation of the two
+// is the pairwise reduction.  No LDS traffic, unlike a lane shuffle.
+#if defined(__HIP_DEVICE_COMPILE__)
+__device__ __forceinline__ float max_across_rows(float x)
+{
+    u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float sum_across_rows(float x)
+{
+    u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+#else // the host pass only parses device code
+__device__ __forceinline__ float max_across_rows(float x) { return x; }
+__device__ __forceinline__ float sum_across_rows(float x) { return x; }
+#endif
+
 __device__ __forceinline__ int clamp_page(int page, int num_pages)
 {
     return min(max(page, 0), num_pages - 1);

@@ -150,8 +150,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
 
     // denominators: sum the four lane groups
     float l = st.l;
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
+    l = sum_across_rows(l);
 
     float *sm = (float *)lds_raw;     // [kWaves][G]
     float *sl = sm + kWaves * G;      // [kWaves][G]

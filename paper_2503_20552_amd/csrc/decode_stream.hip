@@ -384,8 +384,7 @@ __device__ __forceinline__ PairWeights pair_softmax(WaveState &st, PageRegs &pb,
 
     float bm = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
                      fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-    bm = fmaxf(bm, __shfl_xor(bm, 16));
-    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    bm = max_across_rows(bm);
     if (__any(bm > st.m)) {
         const float mn = fmaxf(st.m, bm);
         const float alpha = fast_exp2(st.m - mn);
@@ -804,8 +803,7 @@ void decode_stream_kernel(const StreamParams sp)
             const int use = sp.nb == 2 ? (k >> 1) : k;
             poll_equal(&sh.gen[buf], use, &sh.failed, sp.faults); // the buffer's previous item has been combined
             float l = st.l;
-            l += __shfl_xor(l, 16);
-            l += __shfl_xor(l, 32);
+            l = sum_across_rows(l);
             float *so = staging + (buf * kWaves + wave) * (G * D); // [G][D]
             if (j == 0 && r < G) {
                 sh.ml[buf][wave][r][0] = st.m;

@@ -112,8 +112,7 @@ __device__ __forceinline__ void attend_page(WaveState &st, PageRegs &pg, const u
     }
 
     float bm = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-    bm = fmaxf(bm, __shfl_xor(bm, 16));
-    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    bm = max_across_rows(bm);
     if (__any(bm > st.m)) {
         const float mn = fmaxf(st.m, bm);
         const float alpha = fast_exp2(st.m - mn);
