@@ -385,7 +385,7 @@ __device__ __forceinline__ PairWeights pair_softmax(WaveState &st, PageRegs &pb,
     float bm = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
                      fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
     bm = max_across_rows(bm);
-    if (__any(bm > st.m)) {
+    if (__any(bm > st.m + kMaxSlack)) {
         const float mn = fmaxf(st.m, bm);
         const float alpha = fast_exp2(st.m - mn);
         st.m = mn;

@@ -60,9 +60,17 @@ __device__ __forceinline__ void wait_older_page()
     asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
 }
 
+// The running maximum of the online softmax only has to keep the weights in range, not to be
+// the true maximum: it is moved up (and the accumulators rescaled, the expensive part of a
+// step) only when a score exceeds it by more than this many powers of two, so weights reach
+// 2^8 at most.  Numerator and denominator carry the same stale maximum, so the quotient and
+// the log-sum-exp are unchanged.  With several heads per wave nearly every step of a short
+// partition would otherwise rescale (the chance that one of four running maxima moves).
+constexpr float kMaxSlack = 8.f;
+
 struct WaveState {
     f32x4 o[8]; // O[head 4j+i][8r+e]
-    float m;    // running max of head r (same value in all four lane groups)
+    float m;    // reference maximum of head r (same value in all four lane groups): >= true max - kMaxSlack
     float l;    // this lane's share of head r's denominator
 };
 
@@ -113,7 +121,7 @@ __device__ __forceinline__ void attend_page(WaveState &st, PageRegs &pg, const u
 
     float bm = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
     bm = max_across_rows(bm);
-    if (__any(bm > st.m)) {
+    if (__any(bm > st.m + kMaxSlack)) {
         const float mn = fmaxf(st.m, bm);
         const float alpha = fast_exp2(st.m - mn);
         st.m = mn;
