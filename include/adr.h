@@ -196,6 +196,38 @@ int adr_stream_create_cu_mask(void **stream, const uint32_t *cu_mask, int n_word
 int adr_stream_destroy(void *stream);
 
 /*
+ * Host-side arithmetic of the paper's proxy (no device work, no stream).
+ *
+ * Offloading-ratio bound, Sec. 3.4.1:
+ *   adr_offload_bound_mem   Eq. 1: min(sum_i HBM_p[i] / HBM_d, sum_i BW_p[i] / BW_d) over the n
+ *                           prefill instances serving one decode instance (HOST arrays of n
+ *                           values, any consistent unit).  NaN when a denominator is not positive
+ *                           or an array is missing.
+ *   adr_offload_bound_comp  Eq. 2: (B_max - B_TPOT) / B_TPOT.  NaN when B_TPOT is not positive.
+ *   adr_offload_bound       Eq. 3: the smaller of the two.
+ * adr_need_offload, Algorithm 1 (Sec. 3.4.3): 1 when the new request's attention may be offloaded,
+ *   0 when not, a negative status on a missing array.  `local` / `offloaded` are the decode
+ *   instance's running and offloaded requests; a request is its maximal and its current token
+ *   count.  Read as printed: both conditions compare with strict "<", and the sum of the offloaded
+ *   requests' maximal lengths, which the listing computes, enters neither condition.
+ * adr_graph_capacity, Sec. 3.2.2: the smallest multiple of `interval` that is >= n (at least one
+ *   interval) if it does not exceed max_capacity, else -1: the recorded graph a batch of n rows is
+ *   replayed with, the other rows being padded rows (seq_len 0, position < 0).
+ */
+typedef struct adr_request_tokens {
+    int64_t max_token;  /* prompt plus the most it may generate */
+    int64_t used_token; /* tokens it holds now */
+} adr_request_tokens;
+
+double adr_offload_bound_mem(const double *hbm_prefill, const double *bw_prefill, int n, double hbm_decode,
+                             double bw_decode);
+double adr_offload_bound_comp(double b_max, double b_tpot);
+double adr_offload_bound(double ob_mem, double ob_comp);
+int adr_need_offload(const adr_request_tokens *req, const adr_request_tokens *local, int n_local,
+                     const adr_request_tokens *offloaded, int n_offloaded, double bound);
+int adr_graph_capacity(int n, int interval, int max_capacity);
+
+/*
  * Self-check of the resident-workgroup kernel (ADR_KERNEL_MFMA): its waves hand
  * work to each other through flags in on-chip memory, and every wait on such a
  * flag is bounded.  `*count` (a HOST pointer) receives the number of waits that

@@ -18,6 +18,8 @@ PARTIALS_ONLY = 16
 EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention",
            "adr_decode_merge", "adr_lse_merge", "adr_probe_stream_read", "adr_probe_copy",
            "adr_stream_create_cu_mask", "adr_stream_destroy", "adr_stream_fault_count",
+           "adr_offload_bound_mem", "adr_offload_bound_comp", "adr_offload_bound", "adr_need_offload",
+           "adr_graph_capacity",
            "adr_status_string", "adr_version")
 
 
@@ -25,6 +27,10 @@ class AdrError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         super().__init__("%s: %s (status %d)" % (where, adr_status_string(status), status))
+
+
+class _CRequest(ctypes.Structure):
+    _fields_ = [("max_token", ctypes.c_int64), ("used_token", ctypes.c_int64)]
 
 
 class _CCache(ctypes.Structure):
@@ -72,6 +78,18 @@ def load_library():
     lib.adr_stream_create_cu_mask.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_uint32), i32]
     lib.adr_stream_destroy.restype = i32
     lib.adr_stream_destroy.argtypes = [vp]
+    f64 = ctypes.c_double
+    lib.adr_offload_bound_mem.restype = f64
+    lib.adr_offload_bound_mem.argtypes = [ctypes.POINTER(f64), ctypes.POINTER(f64), i32, f64, f64]
+    lib.adr_offload_bound_comp.restype = f64
+    lib.adr_offload_bound_comp.argtypes = [f64, f64]
+    lib.adr_offload_bound.restype = f64
+    lib.adr_offload_bound.argtypes = [f64, f64]
+    lib.adr_need_offload.restype = i32
+    lib.adr_need_offload.argtypes = [ctypes.POINTER(_CRequest), ctypes.POINTER(_CRequest), i32,
+                                     ctypes.POINTER(_CRequest), i32, f64]
+    lib.adr_graph_capacity.restype = i32
+    lib.adr_graph_capacity.argtypes = [i32, i32, i32]
     lib.adr_stream_fault_count.restype = i32
     lib.adr_stream_fault_count.argtypes = [ctypes.POINTER(ctypes.c_uint64)]
     lib.adr_status_string.restype = ctypes.c_char_p
@@ -98,6 +116,43 @@ def adr_stream_create_cu_mask(cu_bits) -> int:
 
 def adr_stream_destroy(handle: int) -> None:
     _check(load_library().adr_stream_destroy(ctypes.c_void_p(handle)), "adr_stream_destroy")
+
+
+def _requests(pairs):
+    arr = (_CRequest * max(len(pairs), 1))()
+    for i, (mx, used) in enumerate(pairs):
+        arr[i].max_token, arr[i].used_token = int(mx), int(used)
+    return arr
+
+
+def adr_offload_bound_mem(hbm_prefill, bw_prefill, hbm_decode: float, bw_decode: float) -> float:
+    n = len(hbm_prefill)
+    if len(bw_prefill) != n:
+        raise ValueError("one capacity and one bandwidth per prefill instance")
+    f64n = ctypes.c_double * max(n, 1)
+    return float(load_library().adr_offload_bound_mem(f64n(*hbm_prefill), f64n(*bw_prefill), n,
+                                                      hbm_decode, bw_decode))
+
+
+def adr_offload_bound_comp(b_max: float, b_tpot: float) -> float:
+    return float(load_library().adr_offload_bound_comp(b_max, b_tpot))
+
+
+def adr_offload_bound(ob_mem: float, ob_comp: float) -> float:
+    return float(load_library().adr_offload_bound(ob_mem, ob_comp))
+
+
+def adr_need_offload(req, local, offloaded, bound: float) -> bool:
+    """req and the members of local / offloaded are (max_token, used_token) pairs."""
+    rc = load_library().adr_need_offload(_requests([req]), _requests(local), len(local),
+                                         _requests(offloaded), len(offloaded), bound)
+    if rc < 0:
+        raise AdrError(-rc, "adr_need_offload")
+    return bool(rc)
+
+
+def adr_graph_capacity(n: int, interval: int, max_capacity: int) -> int:
+    return int(load_library().adr_graph_capacity(n, interval, max_capacity))
 
 
 def adr_stream_fault_count() -> int:

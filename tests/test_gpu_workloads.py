@@ -70,6 +70,48 @@ def test_workload_5_length_skew_sampled_rows():
     run_workload(5, rows=np.unique(rows).astype(np.int32))
 
 
+def test_workload_5_fp8_cache_append_then_attend_sampled_rows():
+    """The fp8 leg of the skew workload at full size: the pools are quantised with library casts,
+    the step's token is appended by the fp8 append kernel (bytes and scales checked against the
+    oracle's rule on the touched pages), then attention runs as the benchmark runs it and the
+    sampled rows are compared with the oracle on the dequantised values."""
+    wl = W.WORKLOADS[5]
+    b = W.make_batch(wl, device="cuda:0")
+    k8, ks = W.quantize_pool_fp8(b.k_cache, b.used)
+    v8, vs = W.quantize_pool_fp8(b.v_cache, b.used)
+    b.k_cache = b.v_cache = None
+    torch.cuda.empty_cache()
+    lens = b.lens_before
+    long_rows = np.nonzero(lens >= 32768)[0]
+    short_rows = np.nonzero(lens < 32768)[0]
+    rows = np.unique(np.concatenate([long_rows[:2], [long_rows[np.argmax(lens[long_rows])]],
+                                     short_rows[:40]])).astype(np.int32)
+    say("workload 5 fp8: %d sampled rows, %d pages" % (len(rows), b.num_pages))
+    table, pos, seq = dev(b.block_table), dev(b.positions), dev(b.seq_lens)
+    # host copies of the pages the sampled rows' appends touch, before the append
+    pages = b.block_table[rows, b.positions[rows] // 16]
+    before = [t[torch.from_numpy(pages.astype(np.int64)).cuda()].cpu().numpy() for t in (k8, v8, ks, vs)]
+    adr.adr_kv_append(adr.KVCache(k8, v8, ks, vs), b.k_new, b.v_new, table, pos)
+    torch.cuda.synchronize()
+    # the oracle's append on a miniature pool made of just those pages
+    mini_table = np.arange(len(rows), dtype=np.int32)[:, None]
+    kh, vh, ksh, vsh = (a.copy() for a in before)
+    oracle.kv_append(kh, vh, W.bits(b.k_new)[rows], W.bits(b.v_new)[rows], mini_table,
+                     (b.positions[rows] % 16).astype(np.int32), k_scale=ksh, v_scale=vsh)
+    after = [t[torch.from_numpy(pages.astype(np.int64)).cuda()].cpu().numpy() for t in (k8, v8, ks, vs)]
+    assert np.array_equal(after[0], kh) and np.array_equal(after[1], vh)
+    assert np.array_equal(after[2].view(np.uint32), ksh.view(np.uint32))
+    assert np.array_equal(after[3].view(np.uint32), vsh.view(np.uint32))
+
+    out, lse = gpu_attention(b.q, k8, v8, table, seq, wl.scale, partition_tokens=wl.partition_tokens,
+                             out_dtype=torch.float32, max_seq_len=int(b.seq_lens.max()), k_scale=ks, v_scale=vs)
+    ref, ref_lse, _ = oracle.decode_attention(W.bits(b.q), W.bits(k8), W.bits(v8), b.block_table, b.seq_lens,
+                                              wl.scale, k_scale=W.bits(ks), v_scale=W.bits(vs), rows=rows)
+    max_abs, max_rel = compare(out, lse, ref, ref_lse, rows=rows, what="workload 5 fp8")
+    say("workload 5 fp8 max_abs %.3e max_rel %.3e" % (max_abs, max_rel))
+    assert max_abs <= ATOL
+
+
 def test_resident_kernel_reports_no_expired_waits():
     """Runs after the cases above: none of the waves' bounded waits may have expired."""
     assert adr.adr_stream_fault_count() == 0
