@@ -74,21 +74,24 @@ struct WaveState {
     float l;    // this lane's share of head r's denominator
 };
 
-// Eight OCP E4M3 bytes -> eight bf16 (exact: three mantissa bits fit in seven).
-// The hardware conversion gives fp32 pairs; their upper halves are the bf16 values.
+// Eight OCP E4M3 bytes -> eight bf16 (exact: three mantissa bits fit in seven).  gfx950's
+// v_cvt_scalef32_pk_bf16_fp8 turns two bytes into a bf16 pair in one instruction; the scale
+// operand is 1, so nothing is rounded.
+#if defined(__HIP_DEVICE_COMPILE__)
 __device__ __forceinline__ u32x4 fp8x8_to_bf16x8(u32x2 w)
 {
-    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     u32x4 r;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[h], false);
-        const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[h], true);
-        r[2 * h] = __builtin_amdgcn_perm(__float_as_uint(lo[1]), __float_as_uint(lo[0]), 0x07060302u);
-        r[2 * h + 1] = __builtin_amdgcn_perm(__float_as_uint(hi[1]), __float_as_uint(hi[0]), 0x07060302u);
+        r[2 * h] = __builtin_bit_cast(uint32_t, (bf16x2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[h], 1.0f, false));
+        r[2 * h + 1] = __builtin_bit_cast(uint32_t, (bf16x2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[h], 1.0f, true));
     }
     return r;
 }
+#else // the host pass only parses device code
+__device__ __forceinline__ u32x4 fp8x8_to_bf16x8(u32x2 w) { return u32x4{w[0], w[1], 0u, 0u}; }
+#endif
 
 // One page: S = K Q^T, online softmax, O += P V.
 //   ka           A operand of QK^T (see decode_mfma.hip), one register group per step

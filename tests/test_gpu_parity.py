@@ -285,6 +285,43 @@ def test_fp8_append_is_byte_exact_then_attend(d):
         assert compare(out, lse, ref, ref_lse, what="fp8 append+attend %s" % kernel)[0] <= ATOL
 
 
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_fp8_every_finite_code_is_widened_exactly(kernel):
+    """Rows of one token: out = the token's V (weight 1) and lse = its score, so each output
+    element shows how one cache byte was decoded.  V carries all 254 finite codes, K of (row, head)
+    carries one code in the dimension the one-hot query picks.  Neighbouring codes differ by 6 % or
+    more; the bound is the 2^-15 the matrix-core kernel keeps of a weight (here the V scale)."""
+    B, H, d = 32, 8, 128
+    codes = np.arange(256, dtype=np.uint8)
+    finite = ~np.isin(codes, [0x7F, 0xFF])
+    num_pages = B
+    k8 = np.zeros((num_pages, 16, H, d), dtype=np.uint8)
+    v8 = np.zeros((num_pages, 16, H, d), dtype=np.uint8)
+    pick = 5
+    for row in range(B):
+        for h in range(H):
+            c = row * H + h
+            k8[row, 0, h, pick] = c if finite[c] else 0x38           # 0x38 = 1.0
+            vals = codes[(np.arange(d) + 128 * (h & 1)) % 256].copy()
+            vals[~finite[vals]] = 0
+            v8[row, 0, h, :] = vals
+    rng = np.random.default_rng(3)
+    ks = (0.5 + rng.random((num_pages, H))).astype(np.float32)
+    vs = (0.5 + rng.random((num_pages, H))).astype(np.float32)
+    q = torch.zeros((B, H, d), dtype=torch.bfloat16)
+    q[:, :, pick] = 1.0
+    table = np.arange(B, dtype=np.int32)[:, None]
+    seq = np.ones(B, dtype=np.int32)
+    say("fp8 code table kernel=%s" % kernel)
+    out, lse = gpu_attention(dev(q), dev(k8), dev(v8), dev(table), dev(seq), 0.25, flags=KERNELS[kernel],
+                             k_scale=dev(ks), v_scale=dev(vs))
+    ref, ref_lse, _ = oracle.decode_attention(W.bits(q), k8, v8, table, seq, 0.25, k_scale=ks, v_scale=vs)
+    g = out.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(g - ref) <= 4e-5 * np.abs(ref)), np.abs(g - ref).max()
+    lg = lse.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(lg - ref_lse) <= 4e-5 * np.abs(ref_lse) + 1e-30), np.abs(lg - ref_lse).max()
+
+
 def test_graph_replay_matches_eager_on_every_replay():
     """Append + attention + merge of three layers recorded into one HIP graph; the per-step inputs
     live in fixed buffers.  Each replay is checked against the same step run eagerly, with eager
