@@ -196,6 +196,25 @@ int adr_stream_create_cu_mask(void **stream, const uint32_t *cu_mask, int n_word
 int adr_stream_destroy(void *stream);
 
 /*
+ * Copies around the attention call (decode side of Sec. 3.2.1 / 3.2.2); bf16, bit for bit, 16-byte
+ * pieces: d and every row stride (in ELEMENTS) must be multiples of 8, pointers 16-byte aligned.
+ *
+ * adr_pack_qkv -- "grouping qkv": dst[b] = q[b] | k[b] | v[b], i.e. Hq*d, Hkv*d and Hkv*d elements
+ *   side by side in a row of dst (row stride >= (Hq + 2 Hkv) * d), so that the three tensors travel
+ *   as one message and the receiver passes views of that buffer to adr_kv_append and
+ *   adr_decode_attention.  q, k, v: [B][heads][d] with their own row strides.
+ * adr_scatter_rows -- "merging outputs": dst[row_index[i]][0..row_elems) = src[i][0..row_elems) for
+ *   i < n_rows: the rows an executor returned take their places among the rows of the decode
+ *   batch's output (dst has dst_rows rows).  row_index is a DEVICE int32 array; an index outside
+ *   [0, dst_rows) skips that row; equal indices race.
+ */
+int adr_pack_qkv(void *dst, int64_t dst_row_stride, const void *q, int64_t q_row_stride, const void *k,
+                 int64_t k_row_stride, const void *v, int64_t v_row_stride, int B, int Hq, int Hkv, int d,
+                 void *stream);
+int adr_scatter_rows(void *dst, int64_t dst_row_stride, int dst_rows, const void *src, int64_t src_row_stride,
+                     const int32_t *row_index, int n_rows, int row_elems, void *stream);
+
+/*
  * Host-side arithmetic of the paper's proxy (no device work, no stream).
  *
  * Offloading-ratio bound, Sec. 3.4.1:

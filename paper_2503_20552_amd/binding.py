@@ -19,7 +19,7 @@ EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention"
            "adr_decode_merge", "adr_lse_merge", "adr_probe_stream_read", "adr_probe_copy",
            "adr_stream_create_cu_mask", "adr_stream_destroy", "adr_stream_fault_count",
            "adr_offload_bound_mem", "adr_offload_bound_comp", "adr_offload_bound", "adr_need_offload",
-           "adr_graph_capacity",
+           "adr_graph_capacity", "adr_pack_qkv", "adr_scatter_rows",
            "adr_status_string", "adr_version")
 
 
@@ -88,6 +88,10 @@ def load_library():
     lib.adr_need_offload.restype = i32
     lib.adr_need_offload.argtypes = [ctypes.POINTER(_CRequest), ctypes.POINTER(_CRequest), i32,
                                      ctypes.POINTER(_CRequest), i32, f64]
+    lib.adr_pack_qkv.restype = i32
+    lib.adr_pack_qkv.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, vp]
+    lib.adr_scatter_rows.restype = i32
+    lib.adr_scatter_rows.argtypes = [vp, i64, i32, vp, i64, vp, i32, i32, vp]
     lib.adr_graph_capacity.restype = i32
     lib.adr_graph_capacity.argtypes = [i32, i32, i32]
     lib.adr_stream_fault_count.restype = i32
@@ -116,6 +120,33 @@ def adr_stream_create_cu_mask(cu_bits) -> int:
 
 def adr_stream_destroy(handle: int) -> None:
     _check(load_library().adr_stream_destroy(ctypes.c_void_p(handle)), "adr_stream_destroy")
+
+
+def adr_pack_qkv(dst: torch.Tensor, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, stream=None) -> None:
+    """dst [B, >= (Hq+2Hkv)*d] bf16 <- q | k | v (each [B, heads, d], row-strided views allowed)."""
+    qp, qs = _rows_view(q, "q")
+    kp, ks = _rows_view(k, "k")
+    vp_, vs = _rows_view(v, "v")
+    B, Hq, d = q.shape
+    Hkv = k.shape[1]
+    if dst.dtype != torch.bfloat16 or dst.dim() != 2 or dst.shape[0] != B or dst.stride(1) != 1:
+        raise ValueError("dst must be bf16 [B, width] with contiguous rows")
+    if k.shape != v.shape or k.shape[0] != B or k.shape[2] != d or dst.shape[1] < (Hq + 2 * Hkv) * d:
+        raise ValueError("shape mismatch")
+    _check(load_library().adr_pack_qkv(dst.data_ptr(), dst.stride(0), qp, qs, kp, ks, vp_, vs, B, Hq, Hkv, d,
+                                       _stream_handle(stream)), "adr_pack_qkv")
+
+
+def adr_scatter_rows(dst: torch.Tensor, src: torch.Tensor, row_index: torch.Tensor, stream=None) -> None:
+    """dst[row_index[i]] = src[i] for 2-D bf16 tensors with contiguous rows of equal width."""
+    for t in (dst, src):
+        if t.dtype != torch.bfloat16 or t.dim() != 2 or t.stride(1) != 1:
+            raise ValueError("dst and src must be bf16 [rows, width] with contiguous rows")
+    if dst.shape[1] != src.shape[1] or row_index.dtype != torch.int32 or row_index.numel() != src.shape[0]:
+        raise ValueError("shape mismatch")
+    _check(load_library().adr_scatter_rows(dst.data_ptr(), dst.stride(0), dst.shape[0], src.data_ptr(),
+                                           src.stride(0), row_index.data_ptr(), src.shape[0], src.shape[1],
+                                           _stream_handle(stream)), "adr_scatter_rows")
 
 
 def _requests(pairs):

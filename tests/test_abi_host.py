@@ -142,3 +142,23 @@ def test_cu_mask_stream_and_fault_count_reject_bad_arguments():
     assert handle.value is None
     assert lib.adr_stream_destroy(None) == NULL
     assert lib.adr_stream_fault_count(None) == NULL
+
+
+def test_glue_copies_reject_bad_arguments():
+    lib = adr.load_library()
+    def pack(**kw):
+        a = dict(dst=FAKE, ds=6 * 128, q=FAKE, qs=4 * 128, k=FAKE, ks=128, v=FAKE, vs=128, B=3, Hq=4, Hkv=1, d=128)
+        a.update(kw)
+        return lib.adr_pack_qkv(a["dst"], a["ds"], a["q"], a["qs"], a["k"], a["ks"], a["v"], a["vs"], a["B"],
+                                a["Hq"], a["Hkv"], a["d"], None)
+    assert pack(dst=None) == NULL and pack(v=None) == NULL
+    assert pack(d=100) == SHAPE and pack(ds=6 * 128 - 8) == SHAPE and pack(qs=4 * 128 + 4) == SHAPE
+    assert pack(q=FAKE + 8) == SHAPE and pack(B=-1) == SHAPE
+    assert pack(B=0) == 0
+    def scatter(**kw):
+        a = dict(dst=FAKE, ds=256, rows=8, src=FAKE, ss=256, idx=FAKE, n=4, elems=256)
+        a.update(kw)
+        return lib.adr_scatter_rows(a["dst"], a["ds"], a["rows"], a["src"], a["ss"], a["idx"], a["n"], a["elems"], None)
+    assert scatter(idx=None) == NULL and scatter(src=None) == NULL
+    assert scatter(elems=100) == SHAPE and scatter(ds=128) == SHAPE and scatter(ss=260) == SHAPE
+    assert scatter(n=0) == 0

@@ -322,6 +322,51 @@ def test_fp8_every_finite_code_is_widened_exactly(kernel):
     assert np.all(np.abs(lg - ref_lse) <= 4e-5 * np.abs(ref_lse) + 1e-30), np.abs(lg - ref_lse).max()
 
 
+# ---- copies around the attention call -------------------------------------------------------------
+
+def test_pack_qkv_then_views_feed_append_and_attention():
+    """q, k, v grouped into one buffer by the library; the bytes equal the definition, and views of
+    the packed buffer give the same append and attention as the separate tensors."""
+    from oracle import glue_np
+    b = small_case(80, 8, 2, 128, [3, 47, 200, 16])
+    B, Hq, Hkv, d = 4, 8, 2, 128
+    width = (Hq + 2 * Hkv) * d + 64                     # a padded row stride
+    packed = torch.full((B, width), -1.0, dtype=torch.bfloat16, device="cuda:0")
+    q_strided = dev(torch.cat([b.q.reshape(B, -1), torch.zeros(B, 8, dtype=torch.bfloat16)], 1))[:, :Hq * d].view(B, Hq, d)
+    say("pack qkv")
+    adr.adr_pack_qkv(packed, q_strided, dev(b.k_new), dev(b.v_new))
+    torch.cuda.synchronize()
+    want = glue_np.pack_qkv(W.bits(b.q), W.bits(b.k_new), W.bits(b.v_new), width=width,
+                            fill=int(W.bits(torch.tensor([-1.0], dtype=torch.bfloat16))[0]))
+    assert np.array_equal(W.bits(packed), want)
+    qv = packed[:, :Hq * d].view(B, Hq, d)
+    kv = packed[:, Hq * d:(Hq + Hkv) * d].view(B, Hkv, d)
+    vv = packed[:, (Hq + Hkv) * d:(Hq + 2 * Hkv) * d].view(B, Hkv, d)
+    kc1, vc1, kc2, vc2 = dev(b.k_cache), dev(b.v_cache), dev(b.k_cache), dev(b.v_cache)
+    table, pos, seq = dev(b.block_table), dev(b.positions), dev(b.seq_lens)
+    adr.adr_kv_append(adr.KVCache(kc1, vc1), kv, vv, table, pos)
+    adr.adr_kv_append(adr.KVCache(kc2, vc2), dev(b.k_new), dev(b.v_new), table, pos)
+    o1, l1 = gpu_attention(qv, kc1, vc1, table, seq, 0.09)
+    o2, l2 = gpu_attention(dev(b.q), kc2, vc2, table, seq, 0.09)
+    assert torch.equal(kc1.view(torch.int16), kc2.view(torch.int16)) and torch.equal(o1, o2) and torch.equal(l1, l2)
+
+
+def test_scatter_rows_places_returned_rows_in_the_batch():
+    from oracle import glue_np
+    rng = np.random.default_rng(9)
+    rows, n, width = 40, 17, 32 * 128
+    dst = W.randn_bf16((rows, width), 5)
+    src = W.randn_bf16((n, width), 6)
+    index = rng.permutation(rows)[:n].astype(np.int32)
+    index[3] = -1
+    index[9] = rows + 5                                    # outside: skipped
+    d_dst = dev(dst)
+    say("scatter rows")
+    adr.adr_scatter_rows(d_dst, dev(src), dev(index))
+    torch.cuda.synchronize()
+    assert np.array_equal(W.bits(d_dst), glue_np.scatter_rows(W.bits(dst), W.bits(src), index))
+
+
 def test_graph_replay_matches_eager_on_every_replay():
     """Append + attention + merge of three layers recorded into one HIP graph; the per-step inputs
     live in fixed buffers.  Each replay is checked against the same step run eagerly, with eager
