@@ -418,6 +418,52 @@ def test_graph_replay_matches_eager_on_every_replay():
     assert adr.adr_stream_fault_count() == 0
 
 
+def test_graph_recorded_at_a_capacity_serves_smaller_batches_with_padded_rows():
+    """Sec. 3.2.2: graphs exist for batch capacities at an interval; a batch of n rows replays the
+    smallest capacity that holds it, the surplus rows being padded (position < 0: no append;
+    seq_len 0: zero output, no cache read).  One graph recorded at capacity 8 serves n = 8, 5, 1."""
+    interval, cap_max, part = 4, 16, 256
+    lens = np.asarray([700, 33, 1200, 5, 300, 511, 64, 17], dtype=np.int32)
+    cap = adr.adr_graph_capacity(len(lens), interval, cap_max)
+    assert cap == 8 and adr.adr_graph_capacity(5, interval, cap_max) == 8 and adr.adr_graph_capacity(1, interval, cap_max) == 4
+    wl = W.Workload(99, "case", B=cap, Hq=8, Hkv=2, d=128, lengths="given")
+    b = W.make_batch(wl, device="cpu", headroom_tokens=1, seed_offset=71, lens_before=lens)
+    table, q, k_new, v_new = dev(b.block_table), dev(b.q), dev(b.k_new), dev(b.v_new)
+    max_len = int(lens.max()) + 1
+    ws = torch.empty(max(adr.adr_decode_workspace_bytes(cap, 8, 128, max_len, part), 256), dtype=torch.uint8,
+                     device="cuda:0")
+    out = torch.zeros((cap, 8, 128), dtype=torch.float32, device="cuda:0")
+    pos_buf, seq_buf = dev(lens.copy()), dev(lens + 1)
+    kc, vc = dev(b.k_cache), dev(b.v_cache)
+    cache = adr.KVCache(kc, vc)
+
+    def step():
+        adr.adr_kv_append(cache, k_new, v_new, table, pos_buf)
+        adr.adr_decode_attention(out, q, cache, table, seq_buf, b.wl.scale, max_len, part, ws, None, adr.KERNEL_MFMA)
+
+    say("graph at capacity 8, batches of 8, 5 and 1 rows")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    kh, vh = W.bits(b.k_cache).copy(), W.bits(b.v_cache).copy()
+    oracle.kv_append(kh, vh, W.bits(b.k_new), W.bits(b.v_new), b.block_table, lens)
+    for n in (8, 5, 1):
+        pos = lens.copy(); seq = lens + 1
+        pos[n:] = -1; seq[n:] = 0
+        pos_buf.copy_(dev(pos)); seq_buf.copy_(dev(seq))
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        ref, _, _ = oracle.decode_attention(W.bits(b.q), kh, vh, b.block_table, seq.astype(np.int32), b.wl.scale)
+        compare(out, None, ref, None, what="graph capacity 8, n=%d" % n)
+        assert torch.all(out[n:] == 0)
+    assert np.array_equal(W.bits(kc), kh) and np.array_equal(W.bits(vc), vh)   # padded rows appended nothing new
+
+
 def test_resident_kernel_reports_no_expired_waits():
     """Runs after the cases above: none of the waves' bounded waits may have expired."""
     assert adr.adr_stream_fault_count() == 0
