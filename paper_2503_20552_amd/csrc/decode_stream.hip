@@ -972,27 +972,37 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
     hipError_t e = device_info(&dev);
     if (e != hipSuccess)
         return e;
-    // Ring depth: what one workgroup's LDS holds next to the query tiles and the
-    // staging buffers of the group size (one staging buffer only for the widest groups).
-    // An fp8 pass is bound by what one wave per SIMD can compute, not by memory, and
-    // its stages are half the size: where two workgroups fit in a compute unit's LDS
-    // with a ring of two stages each, run two (measured: 1.4x).
+    // LDS plan: the query tiles and the staging buffers of the group size are fixed costs, the
+    // ring takes the rest.  bf16: one workgroup per compute unit, two staging buffers (one for
+    // the widest groups).  fp8: the pass is bound by what one wave per SIMD can compute, not by
+    // memory, and its stages are half the size, so two workgroups share a compute unit where
+    // they fit (measured: 1.4x); a third ring stage is then worth more than the second staging
+    // buffer (measured on ragged lengths: +3 to +9 %).
     const int q_rows = (p.G + 3) / 4 * 4;
-    const int nb = p.G > 8 ? 1 : 2;
-    const size_t fixed = sizeof(Shared) + (size_t)kWaves * 2 * q_rows * (D * 2) +
-                         (size_t)nb * kWaves * p.G * D * sizeof(float);
     const int stage_bytes = fp8 ? Geo<true>::kStage : Geo<false>::kStage;
-    int per_cu = fp8 ? 2 : 1;
-    int stages = 0;
-    for (; per_cu >= 1; --per_cu) {
-        const size_t share = (size_t)kMaxLdsBytes / per_cu;
-        stages = share > fixed ? (int)((share - fixed) / ((size_t)kWaves * stage_bytes)) : 0;
-        if (stages >= 2)
-            break;
+    const int max_stages = fp8 ? Geo<true>::kMaxStages : Geo<false>::kMaxStages;
+    auto fixed_bytes = [&](int staging_buffers) {
+        return sizeof(Shared) + (size_t)kWaves * 2 * q_rows * (D * 2) +
+               (size_t)staging_buffers * kWaves * p.G * D * sizeof(float);
+    };
+    auto stages_for = [&](int workgroups_per_cu, int staging_buffers) {
+        const size_t share = (size_t)kMaxLdsBytes / workgroups_per_cu, fixed = fixed_bytes(staging_buffers);
+        return share > fixed ? std::min((int)((share - fixed) / ((size_t)kWaves * stage_bytes)), max_stages) : 0;
+    };
+    const int nb_default = p.G > 8 ? 1 : 2;
+    int per_cu = 1, nb = nb_default, stages = 0;
+    if (fp8 && stages_for(2, nb_default) >= 3) {
+        per_cu = 2;
+    } else if (fp8 && stages_for(2, 1) >= 3) {
+        per_cu = 2;
+        nb = 1;
+    } else if (fp8 && stages_for(2, nb_default) >= 2) {
+        per_cu = 2;
     }
-    stages = std::min(stages, fp8 ? Geo<true>::kMaxStages : Geo<false>::kMaxStages);
+    stages = stages_for(per_cu, nb);
     if (stages < 2)
         return hipErrorInvalidValue;
+    const size_t fixed = fixed_bytes(nb);
     const size_t lds = (size_t)kWaves * stages * stage_bytes + fixed;
     StreamParams sp;
     sp.d = p;
