@@ -119,18 +119,19 @@ struct alignas(16) Shared {
     int len[kMaxStreamB];
 };
 
-// largest b with pref[b] <= u  (pref is an exclusive prefix sum of length B+1)
+// largest b < B with pref[b] <= u  (pref is an exclusive prefix sum, pref[0] = 0 <= u; B <= 512).
+// Called by a whole wave: sixty-four lanes probe every eighth entry, eight lanes the eight
+// entries of the block found, and the counts of the two ballots give the row -- two LDS round
+// trips instead of the nine of a binary search.
 __device__ __forceinline__ int find_row(const int *pref, int B, int u)
 {
-    int lo = 0, hi = B; // invariant: pref[lo] <= u < pref[hi]
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (__builtin_amdgcn_readfirstlane(pref[mid]) <= u)
-            lo = mid;
-        else
-            hi = mid;
-    }
-    return lo;
+    const int lane = threadIdx.x & 63;
+    const int coarse = lane * 8;
+    const bool below = coarse < B && pref[coarse] <= u;
+    const int block = __popcll(__ballot(below)) - 1;
+    const int fine = block * 8 + (lane & 7);
+    const bool below2 = lane < 8 && fine < B && pref[fine] <= u;
+    return block * 8 + __popcll(__ballot(below2)) - 1;
 }
 
 __device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamParams &sp, int ticket)
@@ -824,44 +825,66 @@ void decode_stream_kernel(const StreamParams sp)
             arrived = __builtin_amdgcn_readfirstlane(arrived);
             lds_order();
             if (arrived == kWaves - 1) {
+                // Two output quads per lane and round; all LDS reads of a round are issued
+                // before anything is computed, so the round costs one LDS latency, not ten.
                 const float *sbase = staging + buf * kWaves * (G * D);
-                for (int idx = lane; idx < G * (D / 4); idx += 64) {
-                    const int g = idx / (D / 4), c4 = (idx - g * (D / 4)) * 4;
-                    float mw[kWaves], M = kNegBig;
+                const int quads = G * (D / 4);
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                for (int base = 0; base < quads; base += 128) {
+                    bool ok[2];
+                    int g[2], c4[2];
+                    f32x2 ml[2][kWaves];
+                    f32x4 x[2][kWaves];
 #pragma unroll
-                    for (int w = 0; w < kWaves; ++w) {
-                        mw[w] = sh.ml[buf][w][g][0];
-                        M = fmaxf(M, mw[w]);
-                    }
-                    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-                    float den = 0.f;
+                    for (int t = 0; t < 2; ++t) {
+                        const int idx = base + 64 * t + lane;
+                        ok[t] = idx < quads;
+                        g[t] = ok[t] ? idx / (D / 4) : 0;
+                        c4[t] = (idx & (D / 4 - 1)) * 4;
 #pragma unroll
-                    for (int w = 0; w < kWaves; ++w) {
-                        const float f = fast_exp2(mw[w] - M);
-                        acc += f * *(const f32x4 *)(sbase + w * (G * D) + g * D + c4);
-                        den += f * sh.ml[buf][w][g][1];
-                    }
-                    const float inv = den > 0.f ? 1.f / den : 0.f;
-                    const f32x4 o = acc * inv;
-                    const float lse = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
-                    const int h = C.kvh * G + g;
-                    if (C.n_parts == 1) {
-                        const int64_t off = ((int64_t)C.b * p.Hq + h) * D + c4;
-                        if (p.out_f32) {
-                            *(f32x4 *)((float *)p.out + off) = o;
-                        } else {
-                            u32x2 packed;
-                            packed[0] = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
-                            packed[1] = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
-                            *(u32x2 *)((uint16_t *)p.out + off) = packed;
+                        for (int w = 0; w < kWaves; ++w) {
+                            ml[t][w] = *(const f32x2 *)&sh.ml[buf][w][g[t]][0];
+                            x[t][w] = *(const f32x4 *)(sbase + w * (G * D) + g[t] * D + c4[t]);
                         }
-                        if (p.lse && c4 == 0)
-                            p.lse[(int64_t)C.b * p.Hq + h] = lse;
-                    } else {
-                        const int64_t row = ((int64_t)C.b * p.max_parts + C.part) * p.Hq + h;
-                        *(f32x4 *)(p.part_o + row * D + c4) = o;
-                        if (c4 == 0)
-                            p.part_lse[row] = lse;
+                    }
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        if (!ok[t])
+                            continue;
+                        float M = kNegBig;
+#pragma unroll
+                        for (int w = 0; w < kWaves; ++w)
+                            M = fmaxf(M, ml[t][w][0]);
+                        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                        float den = 0.f;
+#pragma unroll
+                        for (int w = 0; w < kWaves; ++w) {
+                            const float f = fast_exp2(ml[t][w][0] - M);
+                            acc += f * x[t][w];
+                            den += f * ml[t][w][1];
+                        }
+                        const float inv = den > 0.f ? 1.f / den : 0.f;
+                        const f32x4 o = acc * inv;
+                        const float lse = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
+                        const int h = C.kvh * G + g[t];
+                        if (C.n_parts == 1) {
+                            const int64_t off = ((int64_t)C.b * p.Hq + h) * D + c4[t];
+                            if (p.out_f32) {
+                                *(f32x4 *)((float *)p.out + off) = o;
+                            } else {
+                                u32x2 packed;
+                                packed[0] = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
+                                packed[1] = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
+                                *(u32x2 *)((uint16_t *)p.out + off) = packed;
+                            }
+                            if (p.lse && c4[t] == 0)
+                                p.lse[(int64_t)C.b * p.Hq + h] = lse;
+                        } else {
+                            const int64_t row = ((int64_t)C.b * p.max_parts + C.part) * p.Hq + h;
+                            *(f32x4 *)(p.part_o + row * D + c4[t]) = o;
+                            if (c4[t] == 0)
+                                p.part_lse[row] = lse;
+                        }
                     }
                 }
                 if (lane == 0) {
