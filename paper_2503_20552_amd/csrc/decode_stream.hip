@@ -57,7 +57,8 @@ namespace adr {
 constexpr int kMaxStreamB = 512;
 constexpr int kTicketSlots = 64;
 constexpr int kQueue = 8;          // item records kept in LDS (power of two)
-constexpr int kSpinLimit = 1 << 20; // polls of an LDS word before a wait is declared failed (~0.1 s)
+constexpr int kSpinLimit = 1 << 24; // polls of an LDS word before a wait is declared failed (seconds: an
+                                    // unsplit row of millions of tokens keeps a wave busy for tens of ms)
 constexpr int kSpinLimitAfterFault = 64; // ... once a wait of this workgroup has failed
 
 // Geometry of one ring stage: K tile, V tile, then (fp8) the two scales, each

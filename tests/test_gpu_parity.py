@@ -213,6 +213,17 @@ def test_split_equals_unsplit_within_rounding():
         assert (lw - ls).abs().max().item() < 2e-5
 
 
+@pytest.mark.parametrize("kernel", ["valu", "mfma", "grid"])
+def test_one_long_unsplit_row_among_short_ones(kernel):
+    """A single pass over a 40 000-token row (2 500 pages through one item) next to tiny rows."""
+    b = small_case(43, 8, 2, 128, [39999, 4, 299, 0])
+    say("long unsplit row kernel=%s" % kernel)
+    out, lse = gpu_attention(dev(b.q), dev(b.k_cache), dev(b.v_cache), dev(b.block_table), dev(b.seq_lens),
+                             b.wl.scale, flags=KERNELS[kernel])
+    ref, ref_lse = oracle_attention(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.wl.scale)
+    assert compare(out, lse, ref, ref_lse, what="long row %s" % kernel)[0] <= ATOL
+
+
 # ---- fp8-e4m3 cache -----------------------------------------------------------------
 
 def fp8_case(seed, Hq, Hkv, d, lens):
