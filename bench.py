@@ -57,10 +57,7 @@ def build_state(wl: W.Workload, layers: int, total_steps: int, fp8: bool = False
 
     caches = [as_cache(b.k_cache, b.v_cache)]
     for i in range(1, layers):
-        used = b.used
-        caches.append(as_cache(
-            W.fill_pool_bf16(b.num_pages, wl.page_size, wl.Hkv, wl.d, used, wl.seed + 100 + 2 * i, dev),
-            W.fill_pool_bf16(b.num_pages, wl.page_size, wl.Hkv, wl.d, used, wl.seed + 101 + 2 * i, dev)))
+        caches.append(as_cache(*W.layer_pools(wl, b, i, dev)))
     if fp8:
         b.k_cache = b.v_cache = None                 # the bf16 originals are not needed any more
         torch.cuda.empty_cache()

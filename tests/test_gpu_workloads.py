@@ -57,6 +57,23 @@ def test_workload_3_llama3_8b_gqa_one_layer_all_rows():
     run_workload(3)
 
 
+@pytest.mark.parametrize("layer", [15, 31])
+def test_workload_3_other_resident_layers_all_rows(layer):
+    """The benchmark rotates over 32 layer caches; layers 15 and 31 (their own pool values, the same
+    page table) are checked like layer 0, after the step's append."""
+    wl = W.WORKLOADS[3]
+    b = W.make_batch(wl, device="cuda:0")
+    kc, vc = W.layer_pools(wl, b, layer, "cuda:0")
+    b.k_cache = b.v_cache = None
+    table, pos, seq = dev(b.block_table), dev(b.positions), dev(b.seq_lens)
+    say("workload 3 layer %d" % layer)
+    adr.adr_kv_append(adr.KVCache(kc, vc), b.k_new, b.v_new, table, pos)
+    out, lse = gpu_attention(b.q, kc, vc, table, seq, wl.scale, partition_tokens=wl.partition_tokens,
+                             out_dtype=torch.bfloat16, max_seq_len=int(b.seq_lens.max()))
+    ref, ref_lse = oracle_attention(b.q, kc, vc, b.block_table, b.seq_lens, wl.scale)
+    compare(out, lse, ref, ref_lse, what="workload 3 layer %d" % layer)
+
+
 def test_workload_4_colocation_shape_all_rows():
     run_workload(4)
 

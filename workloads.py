@@ -219,6 +219,15 @@ def make_batch(wl: Workload, device="cpu", headroom_tokens: int = 1, seed_offset
     return Batch(wl, lens_before, bt, num_pages, spare, used, q, k_new, v_new, kc, vc)
 
 
+def layer_pools(wl: Workload, batch: "Batch", layer: int, device="cpu"):
+    """K and V pools of resident layer `layer` (layer 0 is the batch's own pair): same page table and
+    poison pattern, values from the layer's own seeds."""
+    if layer == 0:
+        return batch.k_cache, batch.v_cache
+    return (fill_pool_bf16(batch.num_pages, wl.page_size, wl.Hkv, wl.d, batch.used, wl.seed + 100 + 2 * layer, device),
+            fill_pool_bf16(batch.num_pages, wl.page_size, wl.Hkv, wl.d, batch.used, wl.seed + 101 + 2 * layer, device))
+
+
 def describe_lengths(L: np.ndarray) -> dict:
     L = np.asarray(L)
     return {"min": int(L.min()), "median": float(np.median(L)), "mean": float(L.mean()),
