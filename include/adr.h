@@ -18,6 +18,11 @@
  *    Calls only enqueue kernels: no synchronisation, no allocation, no copies
  *    to the host, grids sized from host scalars only, so a call may be recorded
  *    into a HIP graph (Sec. 3.2.2 relies on replaying pre-launched kernels).
+ *  - Concurrency: calls on different streams of one device may overlap, up to 128 attention
+ *    launches in flight.  A launch recorded into a graph keeps a pair of device counters for all
+ *    its replays (128 such launches can be alive): replays of one recorded graph must not overlap
+ *    each other, and no more than 128 recorded attention launches should exist at a time if
+ *    different graphs may run concurrently.
  *  - Return value: ADR_OK or an error code.  Every host-checkable violation is
  *    reported BEFORE anything is launched and leaves all buffers untouched.
  *  - bf16 = upper 16 bits of IEEE binary32.  fp8 = OCP E4M3 (finite-only

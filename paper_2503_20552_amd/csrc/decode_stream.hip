@@ -55,7 +55,7 @@
 namespace adr {
 
 constexpr int kMaxStreamB = 512;
-constexpr int kTicketSlots = 64;
+constexpr int kTicketSlots = 256; // counter pairs: the lower half serves direct launches, the upper half recorded ones
 constexpr int kQueue = 8;          // item records kept in LDS (power of two)
 constexpr int kSpinLimit = 1 << 24; // polls of an LDS word before a wait is declared failed (seconds: an
                                     // unsplit row of millions of tokens keeps a wave busy for tens of ms)
@@ -940,7 +940,10 @@ void decode_stream_kernel(const StreamParams sp)
 }
 
 namespace {
-std::atomic<unsigned> g_next_slot{0};
+// A launch takes the next counter pair of its half of the pool, round robin.  A recorded launch
+// keeps its pair for every replay, which is why it must not share the pool with direct launches
+// that may run beside a replay on another stream.
+std::atomic<unsigned> g_next_slot{0}, g_next_recorded_slot{0};
 }
 
 bool decode_stream_supports(int d, int G, int B)
@@ -1030,7 +1033,13 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
     const size_t lds = (size_t)kWaves * stages * stage_bytes + fixed;
     StreamParams sp;
     sp.d = p;
-    sp.ticket = g_info[dev].tickets + 2 * (g_next_slot.fetch_add(1) % kTicketSlots);
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capturing) != hipSuccess)
+        (void)hipGetLastError();
+    const unsigned slot = capturing == hipStreamCaptureStatusNone
+                              ? g_next_slot.fetch_add(1) % (kTicketSlots / 2)
+                              : kTicketSlots / 2 + g_next_recorded_slot.fetch_add(1) % (kTicketSlots / 2);
+    sp.ticket = g_info[dev].tickets + 2 * slot;
     sp.faults = g_info[dev].faults;
     sp.pt = p.partition_tokens > 0 ? p.partition_tokens : (1 << 30);
     sp.stages = stages;
@@ -1039,9 +1048,6 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
     // A stream may be confined to some of the compute units: size the grid for those.
     // (Not asked of a stream that is recording a graph: queries can end a capture.)
     int cus = g_info[dev].workgroups;
-    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(stream, &capturing) != hipSuccess)
-        (void)hipGetLastError();
     if (capturing == hipStreamCaptureStatusNone) {
         uint32_t mask[32] = {0};
         if (hipExtStreamGetCUMask(stream, 32, mask) == hipSuccess) {
