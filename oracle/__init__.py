@@ -51,7 +51,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        # ADR_ORACLE_MUTANT names a deliberately broken build of the C file; only the test that
+        # checks that the pins notice such builds sets it.
+        lib = ctypes.CDLL(os.environ.get("ADR_ORACLE_MUTANT") or build())
         lib.oracle_fp8_e4m3_decode.restype = ctypes.c_double
         lib.oracle_fp8_e4m3_decode.argtypes = [ctypes.c_uint8]
         lib.oracle_fp8_e4m3_encode.restype = ctypes.c_uint8

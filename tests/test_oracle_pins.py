@@ -340,7 +340,7 @@ def test_fp8_append_sets_scale_on_slot_zero_and_quantises_with_it():
     P, ps, Hkv, d, B = 6, 16, 2, 64, 3
     kb = np.full((P, ps, Hkv, d), 0x7F, dtype=np.uint8); vb = kb.copy()
     ks = np.full((P, Hkv), np.nan, dtype=np.float32); vs = ks.copy()
-    ks[1] = [0.03125, 0.0625]; vs[1] = [0.015625, 0.5]
+    ks[1] = [0.03125, 0.0625]; vs[1] = [0.00390625, 0.5]
     bt = np.array([[0, 5], [1, 5], [2, 3]], dtype=np.int32)
     pos = np.array([0, 5, 16], dtype=np.int32)                 # slot 0 of page 0; slot 5 of page 1; slot 0 of page 3
     k_new = to_bits(rng.standard_normal((B, Hkv, d))); v_new = to_bits(rng.standard_normal((B, Hkv, d)) * 3)
@@ -359,6 +359,13 @@ def test_fp8_append_sets_scale_on_slot_zero_and_quantises_with_it():
             assert np.all(np.abs(deq - x) <= bound)
             if fresh:                                           # headroom 2x: max lands at 224
                 assert np.max(np.abs(t[kb[page, slot, h]])) == 224.0
+    # a token that does not open a page leaves the page's scales as they were ...
+    assert ks[1].tolist() == [0.03125, 0.0625] and vs[1].tolist() == [0.00390625, 0.5]
+    # ... and what does not fit under the stored scale saturates at the largest finite code
+    xv = f64(v_new[1, 0])
+    over = np.abs(xv) / 0.00390625 > 464.0
+    assert over.any() and np.all(np.abs(t[vb[1, 5, 0]][over]) == 448.0)
+    assert np.all(np.sign(t[vb[1, 5, 0]][over]) == np.sign(xv[over]))
     untouched = np.ones((P, ps), dtype=bool)
     untouched[0, 0] = untouched[1, 5] = untouched[3, 0] = False
     assert np.all(kb[untouched] == 0x7F) and np.all(vb[untouched] == 0x7F)
