@@ -470,7 +470,7 @@ def cpu_baseline(wl, st, step, bytes_per_token):
     b = st["batch"]
     seq = st["seq_lens"][step].cpu().numpy()
     pairs_per_layer = int(seq.sum()) * wl.Hq                 # (token, q-head) dot products and V sums
-    n_layers = int(min(len(st["caches"]), max(1, round(2.5e8 / max(pairs_per_layer, 1)))))
+    n_layers = int(min(len(st["caches"]), max(1, round(4e8 / max(pairs_per_layer, 1)))))
     qh = W.bits(st["q"].contiguous())
     dt, threads = 0.0, 1
     for li in range(n_layers):
