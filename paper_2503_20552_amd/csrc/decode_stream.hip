@@ -470,14 +470,18 @@ __device__ __forceinline__ void read_stage(const char *tile, const uint32_t (&k_
     }
 }
 
-template <bool FP8>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 2)))
+// STAGES > 0 fixes the ring depth at compile time (the depths of the common shapes: ring
+// positions and wait counts become constants); STAGES = 0 takes it from the parameters.
+// An fp8 pass runs two workgroups per compute unit, i.e. two waves per SIMD: its register
+// budget is half the file.
+template <bool FP8, int STAGES>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(FP8 ? 2 : 1, 2)))
 void decode_stream_kernel(const StreamParams sp)
 {
     typedef Geo<FP8> geo;
     constexpr int kStageBytes = geo::kStage;
     const DecodeParams &p = sp.d;
-    const int S = sp.stages;
+    const int S = STAGES > 0 ? STAGES : sp.stages;
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     const int ring_bytes = kWaves * S * kStageBytes;
     const int qtile_bytes = sp.q_rows * (D * 2);
@@ -975,12 +979,11 @@ hipError_t device_info(int *dev_out)
         return e;
     if ((e = hipGetSymbolAddress((void **)&di.faults, HIP_SYMBOL(g_stream_faults))) != hipSuccess)
         return e;
-    if ((e = hipFuncSetAttribute((const void *)decode_stream_kernel<false>,
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes)) != hipSuccess)
-        return e;
-    if ((e = hipFuncSetAttribute((const void *)decode_stream_kernel<true>,
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes)) != hipSuccess)
-        return e;
+    const void *kernels[] = {(const void *)decode_stream_kernel<false, 0>, (const void *)decode_stream_kernel<false, 4>,
+                             (const void *)decode_stream_kernel<true, 0>, (const void *)decode_stream_kernel<true, 3>};
+    for (const void *kernel : kernels)
+        if ((e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes)) != hipSuccess)
+            return e;
     int cus = 0;
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess)
         return e;
@@ -1063,10 +1066,15 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
     int64_t grid = (int64_t)p.B * p.Hkv * p.max_parts;
     if (grid > (int64_t)cus * per_cu)
         grid = (int64_t)cus * per_cu;
-    if (fp8)
-        decode_stream_kernel<true><<<dim3((unsigned)grid), kThreads, lds, stream>>>(sp);
+    const dim3 blocks((unsigned)grid);
+    if (fp8 && stages == 3)
+        decode_stream_kernel<true, 3><<<blocks, kThreads, lds, stream>>>(sp);
+    else if (fp8)
+        decode_stream_kernel<true, 0><<<blocks, kThreads, lds, stream>>>(sp);
+    else if (stages == 4)
+        decode_stream_kernel<false, 4><<<blocks, kThreads, lds, stream>>>(sp);
     else
-        decode_stream_kernel<false><<<dim3((unsigned)grid), kThreads, lds, stream>>>(sp);
+        decode_stream_kernel<false, 0><<<blocks, kThreads, lds, stream>>>(sp);
     return hipGetLastError();
 }
 
