@@ -196,7 +196,8 @@ def main():
     traffic = MEASURED_TRAFFIC_BYTES.get((wl.ident, kernel_name)) if not fp8 else None
     roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "avg_kernel_ms": round(float(attn_ms.mean()), 5), "launches": int(len(attn_ms)),
+                "avg_kernel_ms": round(float(attn_ms.mean()), 5),
+                "median_kernel_ms": round(float(np.median(attn_ms)), 5), "launches": int(len(attn_ms)),
                 "algorithmic_bytes_per_launch": int(bytes_per_launch),
                 "merge_avg_ms": round(float(merge_ms.mean()), 5)}
     log("partition pass %.4f ms avg (min %.4f, max %.4f), merge %.4f ms avg" % (
