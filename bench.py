@@ -4,8 +4,9 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 3] [--kernel auto]
 
 A step is one decode iteration of the attention executor over every resident
-layer: per layer adr_kv_append (the new token) then adr_decode_attention
-(partition pass + log-sum-exp merge).  Sequences grow by one token per step.
+layer: per layer adr_decode_step = the append of the new token, the partition
+pass and the log-sum-exp merge (--separate-append: adr_kv_append, then
+adr_decode_attention).  Sequences grow by one token per step.
 Prints ONE JSON line: whole-job attended-KV bandwidth (algorithmic bytes of K
 and V attended per second, inputs resident in HBM), the roofline of the
 dominant kernel from HIP events on the launch stream, and the fp64 oracle timed
@@ -87,6 +88,8 @@ def main():
     ap.add_argument("--partition", type=int, default=-1, help="partition tokens (-1 = the workload's)")
     ap.add_argument("--cache-dtype", default="bf16", choices=["bf16", "fp8"],
                     help="fp8: caches quantised to e4m3 bytes with one fp32 scale per (page, kv-head)")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="adr_kv_append then adr_decode_attention per layer instead of one adr_decode_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--corun-gemm", action="store_true",
                     help="colocation measurement: the attention steps on one stream while bf16 8192^3 matrix "
@@ -137,15 +140,19 @@ def main():
         if pos is None:
             pos, seq = st["positions"][s], st["seq_lens"][s]
         for li, cache in enumerate(st["caches"]):
-            adr.adr_kv_append(cache, st["k_new"], st["v_new"], st["table"], pos)
+            if args.separate_append:
+                adr.adr_kv_append(cache, st["k_new"], st["v_new"], st["table"], pos)
+                attend = lambda fl: adr.adr_decode_attention(out, st["q"], cache, st["table"], seq, wl.scale,
+                                                             st["max_len"], part, ws, None, fl)
+            else:   # append and attention in one call (the token index is seq - 1 = pos)
+                attend = lambda fl: adr.adr_decode_step(out, st["q"], st["k_new"], st["v_new"], cache, st["table"],
+                                                        seq, wl.scale, st["max_len"], part, ws, None, fl)
             if events is None:
-                adr.adr_decode_attention(out, st["q"], cache, st["table"], seq, wl.scale, st["max_len"],
-                                         part, ws, None, flags)
+                attend(flags)
             else:   # same kernels, same order, with an event between the two passes
                 e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
                 e0.record()
-                adr.adr_decode_attention(out, st["q"], cache, st["table"], seq, wl.scale, st["max_len"],
-                                         part, ws, None, flags | adr.PARTIALS_ONLY)
+                attend(flags | adr.PARTIALS_ONLY)
                 e1.record()
                 adr.adr_decode_merge(out, seq, st["max_len"], part, ws)
                 e2.record()

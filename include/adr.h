@@ -144,6 +144,29 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
                          unsigned flags, void *stream);
 
 /*
+ * adr_decode_step -- one decode step of the executor (Sec. 2.1 steps (1)-(2), Sec. 3.2.1): the
+ * new token's K/V join the cache and the row attends over all its tokens, the new one included.
+ * Same result, in `out`, `lse` and the cache, as
+ *     adr_kv_append(cache, k_new, v_new, new_row_stride, block_table, max_pages_per_req, pos, B, stream)
+ *     with pos[b] = min(max(seq_lens[b], 0), max_seq_len) - 1   (an empty row appends nothing),
+ * followed by adr_decode_attention with the remaining arguments.
+ *
+ *   k_new, v_new  bf16 [B][Hkv][d], rows new_row_stride ELEMENTS apart (views into the grouped
+ *                 q|k|v buffer are fine), 16-byte aligned; read only.
+ *   everything else as in adr_decode_attention; seq_lens is the length AFTER the append.
+ *
+ * The append kernel runs first, then the attention kernels, all on `stream`; the call saves the
+ * caller the positions array (it is seq_lens - 1) and one trip through the binding.  k_new /
+ * v_new must not alias the cache.
+ */
+int adr_decode_step(void *out, adr_dtype out_dtype, float *lse, const void *q, int64_t q_row_stride,
+                    const void *k_new, const void *v_new, int64_t new_row_stride,
+                    const adr_kv_cache *cache, const int32_t *block_table, int max_pages_per_req,
+                    const int32_t *seq_lens, int B, int Hq, float scale, int max_seq_len,
+                    int partition_tokens, void *workspace, size_t workspace_bytes, unsigned flags,
+                    void *stream);
+
+/*
  * adr_decode_merge -- the second pass of a split adr_decode_attention that was
  * called with ADR_PARTIALS_ONLY: merges the partitions left in `workspace` into
  * out / lse for every row with more than one partition; other rows are left as

@@ -15,7 +15,7 @@ ADR_BF16, ADR_FP8_E4M3, ADR_F32 = 0, 1, 2
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_MFMA_GRID = 0, 1, 2, 3
 PARTIALS_ONLY = 16
 
-EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention",
+EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention", "adr_decode_step",
            "adr_decode_merge", "adr_lse_merge", "adr_probe_stream_read", "adr_probe_copy",
            "adr_stream_create_cu_mask", "adr_stream_destroy", "adr_stream_fault_count",
            "adr_offload_bound_mem", "adr_offload_bound_comp", "adr_offload_bound", "adr_need_offload",
@@ -66,6 +66,9 @@ def load_library():
     lib.adr_decode_attention.restype = i32
     lib.adr_decode_attention.argtypes = [vp, i32, vp, vp, i64, ctypes.POINTER(_CCache), vp, i32,
                                          vp, i32, i32, f32, i32, i32, vp, sz, u32, vp]
+    lib.adr_decode_step.restype = i32
+    lib.adr_decode_step.argtypes = [vp, i32, vp, vp, i64, vp, vp, i64, ctypes.POINTER(_CCache), vp, i32,
+                                    vp, i32, i32, f32, i32, i32, vp, sz, u32, vp]
     lib.adr_decode_merge.restype = i32
     lib.adr_decode_merge.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
     lib.adr_lse_merge.restype = i32
@@ -281,14 +284,7 @@ def adr_decode_workspace_bytes(B: int, Hq: int, d: int, max_seq_len: int,
     return int(load_library().adr_decode_workspace_bytes(B, Hq, d, max_seq_len, partition_tokens))
 
 
-def adr_decode_attention(out: torch.Tensor, q: torch.Tensor, cache: KVCache,
-                         block_table: torch.Tensor, seq_lens: torch.Tensor, scale: float,
-                         max_seq_len: int, partition_tokens: int = 0,
-                         workspace: Optional[torch.Tensor] = None,
-                         lse: Optional[torch.Tensor] = None, flags: int = KERNEL_AUTO,
-                         stream=None) -> None:
-    lib = load_library()
-    cs = cache.c_struct()
+def _attention_args(out, q, cache, block_table, seq_lens, workspace, lse):
     qp, qstride = _rows_view(q, "q")
     B, Hq, d = q.shape
     if out.dtype == torch.bfloat16:
@@ -307,11 +303,47 @@ def adr_decode_attention(out: torch.Tensor, q: torch.Tensor, cache: KVCache,
     ws_ptr, ws_bytes = None, 0
     if workspace is not None:
         ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    return odt, (lse.data_ptr() if lse is not None else None), qp, qstride, B, Hq, ws_ptr, ws_bytes
+
+
+def adr_decode_attention(out: torch.Tensor, q: torch.Tensor, cache: KVCache,
+                         block_table: torch.Tensor, seq_lens: torch.Tensor, scale: float,
+                         max_seq_len: int, partition_tokens: int = 0,
+                         workspace: Optional[torch.Tensor] = None,
+                         lse: Optional[torch.Tensor] = None, flags: int = KERNEL_AUTO,
+                         stream=None) -> None:
+    lib = load_library()
+    cs = cache.c_struct()
+    odt, lse_ptr, qp, qstride, B, Hq, ws_ptr, ws_bytes = _attention_args(out, q, cache, block_table, seq_lens,
+                                                                         workspace, lse)
     _check(lib.adr_decode_attention(
-        out.data_ptr(), odt, lse.data_ptr() if lse is not None else None, qp, qstride,
+        out.data_ptr(), odt, lse_ptr, qp, qstride,
         ctypes.byref(cs), _i32(block_table, "block_table"), block_table.shape[1],
         _i32(seq_lens, "seq_lens"), B, Hq, float(scale), int(max_seq_len), int(partition_tokens),
         ws_ptr, ws_bytes, int(flags), _stream_handle(stream)), "adr_decode_attention")
+
+
+def adr_decode_step(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                    cache: KVCache, block_table: torch.Tensor, seq_lens: torch.Tensor, scale: float,
+                    max_seq_len: int, partition_tokens: int = 0,
+                    workspace: Optional[torch.Tensor] = None,
+                    lse: Optional[torch.Tensor] = None, flags: int = KERNEL_AUTO,
+                    stream=None) -> None:
+    lib = load_library()
+    cs = cache.c_struct()
+    odt, lse_ptr, qp, qstride, B, Hq, ws_ptr, ws_bytes = _attention_args(out, q, cache, block_table, seq_lens,
+                                                                         workspace, lse)
+    kp, kstride = _rows_view(k_new, "k_new")
+    vp, vstride = _rows_view(v_new, "v_new")
+    if kstride != vstride:
+        raise ValueError("k_new and v_new must share one row stride")
+    if k_new.shape[0] != B or v_new.shape[0] != B:
+        raise ValueError("k_new / v_new must have one row per request")
+    _check(lib.adr_decode_step(
+        out.data_ptr(), odt, lse_ptr, qp, qstride, kp, vp, kstride,
+        ctypes.byref(cs), _i32(block_table, "block_table"), block_table.shape[1],
+        _i32(seq_lens, "seq_lens"), B, Hq, float(scale), int(max_seq_len), int(partition_tokens),
+        ws_ptr, ws_bytes, int(flags), _stream_handle(stream)), "adr_decode_step")
 
 
 def adr_decode_merge(out: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,

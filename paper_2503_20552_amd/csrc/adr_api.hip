@@ -126,6 +126,8 @@ int adr_kv_append(const adr_kv_cache *cache, const void *k_new, const void *v_ne
     p.new_row_stride = new_row_stride;
     p.block_table = block_table;
     p.positions = positions;
+    p.seq_lens = nullptr;
+    p.max_seq_len = 0;
     p.max_pages = max_pages_per_req;
     p.num_pages = cache->num_pages;
     p.Hkv = cache->Hkv;
@@ -144,18 +146,31 @@ size_t adr_decode_workspace_bytes(int B, int Hq, int d, int max_seq_len, int par
     return round256(rows * d * sizeof(float)) + round256(rows * sizeof(float));
 }
 
-int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q,
-                         int64_t q_row_stride, const adr_kv_cache *cache,
-                         const int32_t *block_table, int max_pages_per_req,
-                         const int32_t *seq_lens, int B, int Hq, float scale, int max_seq_len,
-                         int partition_tokens, void *workspace, size_t workspace_bytes,
-                         unsigned flags, void *stream)
+namespace {
+// The step's new token, when the call appends before it attends (adr_decode_step).
+struct NewToken {
+    const void *k, *v;
+    int64_t row_stride;
+};
+
+int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, int64_t q_row_stride,
+                     const adr_kv_cache *cache, const int32_t *block_table, int max_pages_per_req,
+                     const int32_t *seq_lens, int B, int Hq, float scale, int max_seq_len,
+                     int partition_tokens, void *workspace, size_t workspace_bytes, unsigned flags,
+                     void *stream, const NewToken *nt)
 {
     const int rc = check_cache(cache);
     if (rc != ADR_OK)
         return rc;
     if (!out || !q || !block_table || !seq_lens)
         return ADR_ERR_NULL;
+    if (nt) {
+        if (!nt->k || !nt->v)
+            return ADR_ERR_NULL;
+        if (nt->row_stride < (int64_t)cache->Hkv * cache->d || (nt->row_stride % 8) != 0 ||
+            !aligned16(nt->k) || !aligned16(nt->v))
+            return ADR_ERR_SHAPE;
+    }
     if (B < 0 || Hq <= 0 || max_pages_per_req <= 0 || max_seq_len < 0)
         return ADR_ERR_SHAPE;
     if (Hq % cache->Hkv != 0 || q_row_stride < (int64_t)Hq * cache->d || (q_row_stride % 8) != 0)
@@ -251,6 +266,28 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
     p.out_f32 = out_dtype == ADR_F32;
     p.scale_log2e = scale * adr::kLog2e;
 
+    // The new token goes in first: the append kernel, with the token index taken from seq_lens.
+    if (nt) {
+        adr::AppendParams ap;
+        ap.k_cache = cache->k;
+        ap.v_cache = cache->v;
+        ap.k_scale = cache->k_scale;
+        ap.v_scale = cache->v_scale;
+        ap.k_new = (const uint16_t *)nt->k;
+        ap.v_new = (const uint16_t *)nt->v;
+        ap.new_row_stride = nt->row_stride;
+        ap.block_table = block_table;
+        ap.positions = nullptr;
+        ap.seq_lens = seq_lens;
+        ap.max_seq_len = max_seq_len;
+        ap.max_pages = max_pages_per_req;
+        ap.num_pages = cache->num_pages;
+        ap.Hkv = cache->Hkv;
+        ap.d = d;
+        ap.B = B;
+        if (adr::launch_kv_append(ap, fp8, (hipStream_t)stream) != hipSuccess)
+            return ADR_ERR_LAUNCH;
+    }
     hipError_t e = kernel == MFMA_STREAM ? adr::launch_decode_stream(p, d, fp8, (hipStream_t)stream)
                    : kernel == MFMA_GRID ? adr::launch_decode_mfma(p, d, (hipStream_t)stream)
                                          : adr::launch_decode_valu(p, d, fp8, (hipStream_t)stream);
@@ -276,6 +313,33 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
             return ADR_ERR_LAUNCH;
     }
     return ADR_OK;
+}
+
+} // namespace
+
+int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q,
+                         int64_t q_row_stride, const adr_kv_cache *cache,
+                         const int32_t *block_table, int max_pages_per_req,
+                         const int32_t *seq_lens, int B, int Hq, float scale, int max_seq_len,
+                         int partition_tokens, void *workspace, size_t workspace_bytes,
+                         unsigned flags, void *stream)
+{
+    return decode_attention(out, out_dtype, lse, q, q_row_stride, cache, block_table, max_pages_per_req,
+                            seq_lens, B, Hq, scale, max_seq_len, partition_tokens, workspace,
+                            workspace_bytes, flags, stream, nullptr);
+}
+
+int adr_decode_step(void *out, adr_dtype out_dtype, float *lse, const void *q, int64_t q_row_stride,
+                    const void *k_new, const void *v_new, int64_t new_row_stride,
+                    const adr_kv_cache *cache, const int32_t *block_table, int max_pages_per_req,
+                    const int32_t *seq_lens, int B, int Hq, float scale, int max_seq_len,
+                    int partition_tokens, void *workspace, size_t workspace_bytes, unsigned flags,
+                    void *stream)
+{
+    const NewToken nt = {k_new, v_new, new_row_stride};
+    return decode_attention(out, out_dtype, lse, q, q_row_stride, cache, block_table, max_pages_per_req,
+                            seq_lens, B, Hq, scale, max_seq_len, partition_tokens, workspace,
+                            workspace_bytes, flags, stream, &nt);
 }
 
 int adr_decode_merge(void *out, adr_dtype out_dtype, float *lse, const int32_t *seq_lens, int B,

@@ -58,8 +58,19 @@ struct AppendParams {
     const uint16_t *k_new, *v_new;
     int64_t new_row_stride; // elements between request rows of k_new / v_new
     const int32_t *block_table, *positions;
+    // positions == nullptr: the token index is min(max(seq_lens[b], 0), max_seq_len) - 1
+    // (the last token of the row as the attention kernels see it; an empty row is skipped)
+    const int32_t *seq_lens;
+    int max_seq_len;
     int max_pages, num_pages, Hkv, d, B;
 };
+
+__device__ __forceinline__ int append_position(const AppendParams &p, int b)
+{
+    if (p.positions)
+        return p.positions[b];
+    return min(max(p.seq_lens[b], 0), p.max_seq_len) - 1;
+}
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }

@@ -507,13 +507,18 @@ void decode_stream_kernel(const StreamParams sp)
     // ---- partitions per row: exclusive prefix sums over the rows, four rows per thread
     {
         int f[4], g[4], sf = 0, sg = 0;
+        int given[4]; // read without a condition (a row past the end re-reads the last one), so that
+                      // the four reads are in flight together instead of one after the other
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            given[i] = p.seq_lens[min(tid * 4 + i, B - 1)];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = tid * 4 + i;
             int L = 0;
             f[i] = g[i] = 0;
             if (row < B) {
-                L = max(min(p.seq_lens[row], p.max_seq_len), 0);
+                L = max(min(given[i], p.max_seq_len), 0);
                 sh.len[row] = L;
                 f[i] = L / sp.pt;
                 g[i] = (L % sp.pt != 0 || L == 0) ? 1 : 0; // an empty row still owns one (empty) item

@@ -4,20 +4,29 @@
 namespace adr {
 
 // bf16 cache: one workgroup per request copies the Hkv*d bf16 of K and of V in
-// 16-byte pieces.  The destination row of a token is contiguous.
+// 16-byte pieces.  The destination row of a token is contiguous.  The first pieces are
+// read before the position and the page are looked up (they depend on neither), so the
+// kernel is two memory round trips deep, not three.
 __global__ __launch_bounds__(128) void kv_append_bf16_kernel(const AppendParams p)
 {
     const int b = blockIdx.x;
-    const int pos = p.positions[b];
+    const int row = p.Hkv * p.d; // elements
+    const int64_t src = (int64_t)b * p.new_row_stride;
+    const int first = min((int)threadIdx.x * 8, row - 8);
+    const u32x4 k0 = *(const u32x4 *)(p.k_new + src + first);
+    const u32x4 v0 = *(const u32x4 *)(p.v_new + src + first);
+    const int pos = append_position(p, b);
     if (pos < 0 || pos / kPageSize >= p.max_pages)
         return;
     const int page = p.block_table[(int64_t)b * p.max_pages + pos / kPageSize];
     if (page < 0 || page >= p.num_pages)
         return;
-    const int row = p.Hkv * p.d; // elements
     const int64_t dst = ((int64_t)page * kPageSize + pos % kPageSize) * row;
-    const int64_t src = (int64_t)b * p.new_row_stride;
-    for (int i = threadIdx.x * 8; i < row; i += 128 * 8) {
+    if ((int)threadIdx.x * 8 < row) {
+        *(u32x4 *)((uint16_t *)p.k_cache + dst + first) = k0;
+        *(u32x4 *)((uint16_t *)p.v_cache + dst + first) = v0;
+    }
+    for (int i = threadIdx.x * 8 + 128 * 8; i < row; i += 128 * 8) {
         *(u32x4 *)((uint16_t *)p.k_cache + dst + i) = *(const u32x4 *)(p.k_new + src + i);
         *(u32x4 *)((uint16_t *)p.v_cache + dst + i) = *(const u32x4 *)(p.v_new + src + i);
     }
@@ -55,7 +64,7 @@ template <int D>
 __global__ __launch_bounds__(64) void kv_append_fp8_kernel(const AppendParams p)
 {
     const int b = blockIdx.x / p.Hkv, h = blockIdx.x % p.Hkv;
-    const int pos = p.positions[b];
+    const int pos = append_position(p, b);
     if (pos < 0 || pos / kPageSize >= p.max_pages)
         return;
     const int page = p.block_table[(int64_t)b * p.max_pages + pos / kPageSize];

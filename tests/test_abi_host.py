@@ -109,6 +109,26 @@ def test_append_rejects_bad_arguments():
     assert call(B=0) == 0
 
 
+def test_decode_step_rejects_bad_arguments():
+    """adr_decode_step checks the new token's arguments on top of the attention's, before any launch."""
+    lib = adr.load_library()
+    c = cache()
+
+    def call(**kw):
+        a = dict(out=FAKE, q=FAKE, k_new=FAKE, v_new=FAKE, stride=2 * 128, bt=FAKE, seq=FAKE, B=2, Hq=8,
+                 max_seq_len=64, part=0)
+        a.update(kw)
+        return lib.adr_decode_step(a["out"], adr.ADR_BF16, None, a["q"], 8 * 128, a["k_new"], a["v_new"],
+                                   a["stride"], ctypes.byref(c), a["bt"], 4, a["seq"], a["B"], a["Hq"], 0.1,
+                                   a["max_seq_len"], a["part"], None, 0, 0, None)
+    assert call(k_new=None) == NULL and call(v_new=None) == NULL
+    assert call(out=None) == NULL and call(seq=None) == NULL and call(bt=None) == NULL
+    assert call(stride=128) == SHAPE and call(stride=2 * 128 + 4) == SHAPE and call(k_new=FAKE + 2) == SHAPE
+    assert call(Hq=7) == SHAPE and call(max_seq_len=65) == SHAPE
+    assert call(part=16) == WORK
+    assert call(B=0) == 0
+
+
 def test_merge_rejects_bad_arguments():
     lib = adr.load_library()
 
