@@ -2,7 +2,7 @@
 //
 // One group of d/4 threads per (request, head) row; each thread owns four
 // consecutive output elements (16-byte loads of the fp32 partials).  One sweep
-// over the row's partitions, eight at a time with all their loads issued before
+// over the row's partitions, sixteen at a time with all their loads issued before
 // any is used, carrying a running maximum of the lse values (fixed order, so the
 // result is the same from run to run).
 #include "adr_device.h"
@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(const MergeParams p)
             return; // the attention kernel already wrote this row's final result
     }
 
-    constexpr int CH = 8;
+    constexpr int CH = 16;
     float top = -INFINITY, total = 0.f;
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int i0 = 0; i0 < count; i0 += CH) {
