@@ -36,7 +36,7 @@ HBM_PEAK_GBS = 8000.0
 # WRITE_SIZE runs of this command (see profiles/), scaled by the same counters'
 # reading on adr_probe_copy.  None until such a run has been recorded.
 MEASURED_TRAFFIC_BYTES = {
-    (3, "decode_stream_kernel"): 2341300800,   # profiles/decode_stream_kernel_workload3.md
+    (3, "decode_stream_kernel"): 2344157166,   # profiles/decode_stream_kernel_workload3.md
     (3, "decode_mfma_kernel"): 2338000000,     # profiles/decode_mfma_kernel_workload3.md
 }
 
@@ -140,19 +140,20 @@ def main():
         if pos is None:
             pos, seq = st["positions"][s], st["seq_lens"][s]
         for li, cache in enumerate(st["caches"]):
-            if args.separate_append:
-                adr.adr_kv_append(cache, st["k_new"], st["v_new"], st["table"], pos)
-                attend = lambda fl: adr.adr_decode_attention(out, st["q"], cache, st["table"], seq, wl.scale,
-                                                             st["max_len"], part, ws, None, fl)
-            else:   # append and attention in one call (the token index is seq - 1 = pos)
-                attend = lambda fl: adr.adr_decode_step(out, st["q"], st["k_new"], st["v_new"], cache, st["table"],
-                                                        seq, wl.scale, st["max_len"], part, ws, None, fl)
+            if events is None and not args.separate_append:
+                # append and attention in one call (the token index is seq - 1 = pos)
+                adr.adr_decode_step(out, st["q"], st["k_new"], st["v_new"], cache, st["table"], seq, wl.scale,
+                                    st["max_len"], part, ws, None, flags)
+                continue
+            adr.adr_kv_append(cache, st["k_new"], st["v_new"], st["table"], pos)
             if events is None:
-                attend(flags)
-            else:   # same kernels, same order, with an event between the two passes
+                adr.adr_decode_attention(out, st["q"], cache, st["table"], seq, wl.scale, st["max_len"],
+                                         part, ws, None, flags)
+            else:   # the same three kernels in the same order, with events around the partition pass and the merge
                 e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
                 e0.record()
-                attend(flags | adr.PARTIALS_ONLY)
+                adr.adr_decode_attention(out, st["q"], cache, st["table"], seq, wl.scale, st["max_len"],
+                                         part, ws, None, flags | adr.PARTIALS_ONLY)
                 e1.record()
                 adr.adr_decode_merge(out, seq, st["max_len"], part, ws)
                 e2.record()
