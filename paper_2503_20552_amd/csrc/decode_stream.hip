@@ -985,6 +985,7 @@ hipError_t device_info(int *dev_out)
     if ((e = hipGetSymbolAddress((void **)&di.faults, HIP_SYMBOL(g_stream_faults))) != hipSuccess)
         return e;
     const void *kernels[] = {(const void *)decode_stream_kernel<false, 0>, (const void *)decode_stream_kernel<false, 4>,
+                             (const void *)decode_stream_kernel<false, 3>,
                              (const void *)decode_stream_kernel<true, 0>, (const void *)decode_stream_kernel<true, 3>};
     for (const void *kernel : kernels)
         if ((e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes)) != hipSuccess)
@@ -1078,6 +1079,8 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
         decode_stream_kernel<true, 0><<<blocks, kThreads, lds, stream>>>(sp);
     else if (stages == 4)
         decode_stream_kernel<false, 4><<<blocks, kThreads, lds, stream>>>(sp);
+    else if (stages == 3) // groups of five to eight heads
+        decode_stream_kernel<false, 3><<<blocks, kThreads, lds, stream>>>(sp);
     else
         decode_stream_kernel<false, 0><<<blocks, kThreads, lds, stream>>>(sp);
     return hipGetLastError();
