@@ -27,7 +27,7 @@
  *    reported BEFORE anything is launched and leaves all buffers untouched.
  *  - bf16 = upper 16 bits of IEEE binary32.  fp8 = OCP E4M3 (finite-only
  *    variant: bias 7, max 448, S.1111.111 = NaN).
- *  - Supported set: d in {64, 128}; page_size = 16; Hq a multiple of Hkv with
+ *  - Supported set: d in {64, 128}; page_size in {16, 32, 64}; Hq a multiple of Hkv with
  *    G = Hq/Hkv <= 16; cache dtype bf16 or fp8-e4m3; output bf16 or fp32.
  *    q-head h reads kv-head h / G.
  *  - Alignment: q, k_new, v_new, the caches and `out` must be 16-byte aligned

@@ -27,7 +27,7 @@ int check_cache(const adr_kv_cache *c)
         return ADR_ERR_NULL;
     if (c->num_pages <= 0 || c->Hkv <= 0)
         return ADR_ERR_SHAPE;
-    if (c->page_size != adr::kPageSize || (c->d != 64 && c->d != 128))
+    if ((c->page_size != 16 && c->page_size != 32 && c->page_size != 64) || (c->d != 64 && c->d != 128))
         return ADR_ERR_UNSUPPORTED;
     if (c->dtype != ADR_BF16 && c->dtype != ADR_FP8_E4M3)
         return ADR_ERR_UNSUPPORTED;
@@ -128,6 +128,7 @@ int adr_kv_append(const adr_kv_cache *cache, const void *k_new, const void *v_ne
     p.positions = positions;
     p.seq_lens = nullptr;
     p.max_seq_len = 0;
+    p.page_size = cache->page_size;
     p.max_pages = max_pages_per_req;
     p.num_pages = cache->num_pages;
     p.Hkv = cache->Hkv;
@@ -177,11 +178,11 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
         return ADR_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(out))
         return ADR_ERR_SHAPE;
-    if ((int64_t)max_seq_len > (int64_t)max_pages_per_req * adr::kPageSize)
+    if ((int64_t)max_seq_len > (int64_t)max_pages_per_req * cache->page_size)
         return ADR_ERR_SHAPE; // the table cannot describe that many tokens
     if (out_dtype != ADR_BF16 && out_dtype != ADR_F32)
         return ADR_ERR_UNSUPPORTED;
-    if (partition_tokens < 0 || partition_tokens % adr::kPageSize != 0)
+    if (partition_tokens < 0 || partition_tokens % cache->page_size != 0)
         return ADR_ERR_SHAPE;
     if (flags & ~(0xFu | ADR_PARTIALS_ONLY))
         return ADR_ERR_UNSUPPORTED;
@@ -255,6 +256,7 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
         p.part_lse = (float *)((char *)workspace + round256(rows * d * sizeof(float)));
     }
     p.max_pages = max_pages_per_req;
+    p.page_shift = cache->page_size == 16 ? 0 : cache->page_size == 32 ? 1 : 2;
     p.B = B;
     p.Hq = Hq;
     p.Hkv = cache->Hkv;
@@ -280,6 +282,7 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
         ap.positions = nullptr;
         ap.seq_lens = seq_lens;
         ap.max_seq_len = max_seq_len;
+        ap.page_size = cache->page_size;
         ap.max_pages = max_pages_per_req;
         ap.num_pages = cache->num_pages;
         ap.Hkv = cache->Hkv;

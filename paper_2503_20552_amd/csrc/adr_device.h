@@ -7,7 +7,8 @@
 
 namespace adr {
 
-constexpr int kPageSize = 16;       // tokens per cache page (the only supported size)
+constexpr int kPageSize = 16;       // tokens per tile, the kernels' unit of work: a cache page of 16 << page_shift
+                                    // tokens is 1 << page_shift consecutive tiles of the pool
 constexpr int kWaves = 4;           // waves per workgroup in the attention kernels
 constexpr int kThreads = kWaves * 64;
 constexpr float kLog2e = 1.4426950408889634f;
@@ -33,6 +34,7 @@ struct DecodeParams {
     float *part_o;   // [B][max_parts][Hq][d] normalised partial outputs (split pass)
     float *part_lse; // [B][max_parts][Hq] natural-log lse of each partition
     int max_pages;   // row length of block_table
+    int page_shift;  // log2(page_size / 16)
     int B, Hq, Hkv, G, num_pages;
     int partition_tokens; // 0 = whole sequence in one pass
     int max_parts;        // partitions per request the grid was sized for (>= 1)
@@ -62,7 +64,7 @@ struct AppendParams {
     // (the last token of the row as the attention kernels see it; an empty row is skipped)
     const int32_t *seq_lens;
     int max_seq_len;
-    int max_pages, num_pages, Hkv, d, B;
+    int max_pages, num_pages, page_size, Hkv, d, B;
 };
 
 __device__ __forceinline__ int append_position(const AppendParams &p, int b)
@@ -141,6 +143,14 @@ __device__ __forceinline__ float sum_across_rows(float x) { return x; }
 __device__ __forceinline__ int clamp_page(int page, int num_pages)
 {
     return min(max(page, 0), num_pages - 1);
+}
+
+// Tile `tile` of a row, as an index among all 16-token tiles of the pool: the row's table entry
+// for the page the tile lies in (clamped into the pool), times the tiles of a page, plus the
+// tile's place in its page.
+__device__ __forceinline__ int pool_tile(int table_entry, int tile, int num_pages, int page_shift)
+{
+    return (clamp_page(table_entry, num_pages) << page_shift) | (tile & ((1 << page_shift) - 1));
 }
 
 // Number of partitions of a row of L tokens (>= 1, so that an empty row still

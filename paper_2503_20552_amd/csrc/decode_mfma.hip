@@ -117,13 +117,15 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
         PageRegs A, B;
         u32x4 ka[4];
         const int last = pg + (pg_end - 1 - pg) / kWaves * kWaves; // this wave's last page
-        int page = clamp_page(bt[pg], p.num_pages);
-        int page_next = clamp_page(bt[min(pg + kWaves, last)], p.num_pages);
+        const int sh = p.page_shift; // a cache page is 1 << sh tiles of 16 tokens
+#define ADR_TILE(T) pool_tile(bt[(T) >> sh], (T), p.num_pages, sh)
+        int page = ADR_TILE(pg);
+        int page_next = ADR_TILE(min(pg + kWaves, last));
         load_page(A, tile0, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes), k_lane,
                   v_lane, tok_bytes);
         for (;;) {
             page = page_next;
-            page_next = clamp_page(bt[min(pg + 2 * kWaves, last)], p.num_pages);
+            page_next = ADR_TILE(min(pg + 2 * kWaves, last));
             load_page(B, tile1, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes),
                       k_lane, v_lane, tok_bytes);
             wait_older_page();
@@ -133,7 +135,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
             if (pg >= pg_end)
                 break;
             page = page_next;
-            page_next = clamp_page(bt[min(pg + 2 * kWaves, last)], p.num_pages);
+            page_next = ADR_TILE(min(pg + 2 * kWaves, last));
             load_page(A, tile0, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes),
                       k_lane, v_lane, tok_bytes);
             wait_older_page();
@@ -143,6 +145,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
             if (pg >= pg_end)
                 break;
         }
+#undef ADR_TILE
     }
     // the K tiles are dead from here on; the same LDS now carries the per-wave results
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

@@ -625,6 +625,9 @@ void decode_stream_kernel(const StreamParams sp)
     const __amdgpu_buffer_rsrc_t vs_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(FP8 ? (const void *)p.v_scale : (const void *)kc), 0, scale_range, 0x00020000);
     const int pages_per_part = sp.pt / kPageSize; // 2^26 when the pass is not split (part is 0 then)
+    // "Page" below is a 16-token tile of the pool; a cache page is 1 << tsh of them (the
+    // instantiations with a fixed ring depth serve 16-token pages only).
+    const int tsh = STAGES > 0 ? 0 : p.page_shift;
 
     Item C = fetch(sh.rec[0], 0, &sh.failed, sp.faults);
     Item N = fetch(sh.rec[1], 1, &sh.failed, sp.faults);
@@ -653,7 +656,7 @@ void decode_stream_kernel(const StreamParams sp)
         }                                                                                         \
         ld_ok = ld_pg < ld_end;                                                                   \
         if (ld_ok)                                                                                \
-            ld_id = clamp_page(ld_bt[ld_pg], p.num_pages);                                        \
+            ld_id = pool_tile(ld_bt[ld_pg >> tsh], ld_pg, p.num_pages, tsh);                      \
     } while (0)
     // Ring state: `occ` slots starting at `head` are occupied, in issue order; the
     // next load group goes to `tail`.  real_mask marks the slots that hold a page.
@@ -671,7 +674,7 @@ void decode_stream_kernel(const StreamParams sp)
         if (ld_ok) {                                                                              \
             pend_id = ld_id;                                                                      \
             pend_head = ld_head;                                                                  \
-            pend_scale = (uint32_t)(ld_id * Hkv + ld_kvh) * 4u;                                   \
+            pend_scale = (uint32_t)((ld_id >> tsh) * Hkv + ld_kvh) * 4u;                          \
             issue_half<FP8, 0>(pend_tile, page_rsrc(kc, ld_id, page_bytes), ks_rsrc, k_lane,      \
                                s_lane, pend_head, pend_scale);                                    \
             real_mask |= 1 << tail;                                                               \
@@ -1073,13 +1076,14 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
     if (grid > (int64_t)cus * per_cu)
         grid = (int64_t)cus * per_cu;
     const dim3 blocks((unsigned)grid);
-    if (fp8 && stages == 3)
+    const bool fixed_depth = p.page_shift == 0;
+    if (fp8 && stages == 3 && fixed_depth)
         decode_stream_kernel<true, 3><<<blocks, kThreads, lds, stream>>>(sp);
     else if (fp8)
         decode_stream_kernel<true, 0><<<blocks, kThreads, lds, stream>>>(sp);
-    else if (stages == 4)
+    else if (stages == 4 && fixed_depth)
         decode_stream_kernel<false, 4><<<blocks, kThreads, lds, stream>>>(sp);
-    else if (stages == 3) // groups of five to eight heads
+    else if (stages == 3 && fixed_depth) // groups of five to eight heads
         decode_stream_kernel<false, 3><<<blocks, kThreads, lds, stream>>>(sp);
     else
         decode_stream_kernel<false, 0><<<blocks, kThreads, lds, stream>>>(sp);

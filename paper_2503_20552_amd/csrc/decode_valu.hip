@@ -104,7 +104,7 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(const DecodeParam
     const int pg_end = (t1 + kPageSize - 1) / kPageSize;
 
     for (int pg = t0 / kPageSize + wave; pg < pg_end; pg += kWaves) {
-        const int page = clamp_page(bt[pg], p.num_pages);
+        const int page = pool_tile(bt[pg >> p.page_shift], pg, p.num_pages, p.page_shift); // a 16-token tile
         const int64_t base = ((int64_t)page * kPageSize * Hkv + kvh) * D + c * 8;
         Row8<FP8> kr[U], vr[U];
 #pragma unroll
@@ -115,8 +115,8 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(const DecodeParam
             vr[u].load(p.v_cache, base + (u * TPL + j) * tok_stride);
         float k_scale = 1.f, v_scale = 1.f;
         if (FP8) {
-            k_scale = p.k_scale[(int64_t)page * Hkv + kvh];
-            v_scale = p.v_scale[(int64_t)page * Hkv + kvh];
+            k_scale = p.k_scale[(int64_t)(page >> p.page_shift) * Hkv + kvh];
+            v_scale = p.v_scale[(int64_t)(page >> p.page_shift) * Hkv + kvh];
         }
 
         float s[U][G];

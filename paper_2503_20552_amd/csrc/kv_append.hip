@@ -16,12 +16,12 @@ __global__ __launch_bounds__(128) void kv_append_bf16_kernel(const AppendParams 
     const u32x4 k0 = *(const u32x4 *)(p.k_new + src + first);
     const u32x4 v0 = *(const u32x4 *)(p.v_new + src + first);
     const int pos = append_position(p, b);
-    if (pos < 0 || pos / kPageSize >= p.max_pages)
+    if (pos < 0 || pos / p.page_size >= p.max_pages)
         return;
-    const int page = p.block_table[(int64_t)b * p.max_pages + pos / kPageSize];
+    const int page = p.block_table[(int64_t)b * p.max_pages + pos / p.page_size];
     if (page < 0 || page >= p.num_pages)
         return;
-    const int64_t dst = ((int64_t)page * kPageSize + pos % kPageSize) * row;
+    const int64_t dst = ((int64_t)page * p.page_size + pos % p.page_size) * row;
     if ((int)threadIdx.x * 8 < row) {
         *(u32x4 *)((uint16_t *)p.k_cache + dst + first) = k0;
         *(u32x4 *)((uint16_t *)p.v_cache + dst + first) = v0;
@@ -65,19 +65,19 @@ __global__ __launch_bounds__(64) void kv_append_fp8_kernel(const AppendParams p)
 {
     const int b = blockIdx.x / p.Hkv, h = blockIdx.x % p.Hkv;
     const int pos = append_position(p, b);
-    if (pos < 0 || pos / kPageSize >= p.max_pages)
+    if (pos < 0 || pos / p.page_size >= p.max_pages)
         return;
-    const int page = p.block_table[(int64_t)b * p.max_pages + pos / kPageSize];
+    const int page = p.block_table[(int64_t)b * p.max_pages + pos / p.page_size];
     if (page < 0 || page >= p.num_pages)
         return;
-    const int slot = pos % kPageSize;
+    const int slot = pos % p.page_size;
     constexpr int E = D / 64;
     const int lane = threadIdx.x;
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
         const uint16_t *src = (which ? p.v_new : p.k_new) + (int64_t)b * p.new_row_stride + h * D;
         uint8_t *dst = (uint8_t *)(which ? p.v_cache : p.k_cache) +
-                       (((int64_t)page * kPageSize + slot) * p.Hkv + h) * D;
+                       (((int64_t)page * p.page_size + slot) * p.Hkv + h) * D;
         float *scales = which ? p.v_scale : p.k_scale;
         float x[E];
 #pragma unroll

@@ -77,12 +77,19 @@ def test_decode_attention_rejects_bad_arguments(kw, expect):
 
 @pytest.mark.parametrize("kw,expect", [
     (dict(k=None), NULL), (dict(v=None), NULL), (dict(num_pages=0), SHAPE), (dict(Hkv=0), SHAPE),
-    (dict(page_size=32), UNSUP), (dict(d=96), UNSUP), (dict(dtype=adr.ADR_F32), UNSUP),
+    (dict(page_size=48), UNSUP), (dict(page_size=128), UNSUP), (dict(d=96), UNSUP), (dict(dtype=adr.ADR_F32), UNSUP),
     (dict(dtype=adr.ADR_FP8_E4M3), NULL),      # fp8 without scales
     (dict(k=FAKE + 4), SHAPE),
 ])
 def test_cache_descriptor_is_validated(kw, expect):
     assert attention(cache(**kw)) == expect
+
+
+def test_pages_of_32_and_64_tokens_are_accepted_and_bound_the_partition_size():
+    assert attention(cache(page_size=32), B=0) == 0 and attention(cache(page_size=64), B=0) == 0
+    assert attention(cache(page_size=32), partition_tokens=48) == SHAPE      # not a multiple of the page size
+    assert attention(cache(page_size=32), max_seq_len=129) == SHAPE          # 4 pages name 128 tokens
+    assert attention(cache(page_size=32), max_seq_len=128, B=0) == 0
 
 
 def test_mfma_only_for_d128_and_valu_only_for_small_groups():
