@@ -67,7 +67,14 @@ enum {
      * adr_decode_merge call on the same workspace (rows with one partition are
      * still written to `out` directly).  Lets a caller place the two passes on
      * a stream itself, e.g. to time them separately. */
-    ADR_PARTIALS_ONLY = 16
+    ADR_PARTIALS_ONLY = 16,
+    /* Every partition is attended as an item of its own.  Without this flag the resident
+     * matrix-core kernel, when a pass has many thousands of partitions, takes runs of two or
+     * four neighbouring partitions of a row as one item: the run's result stands in the
+     * workspace at its first partition's place and the others are marked empty (lse = -inf),
+     * which the merge skips.  The final result is the same up to the order of the
+     * floating-point sums; the choice depends on the inputs alone. */
+    ADR_SINGLE_PARTITION_ITEMS = 32
 };
 
 /* The paged KV cache of ONE layer ("cache blocks", Sec. 3.2.1).  K and V are
@@ -128,8 +135,8 @@ size_t adr_decode_workspace_bytes(int B, int Hq, int d, int max_seq_len, int par
  *              tokens, attended independently, and merged by log-sum-exp; needs
  *              `workspace` of adr_decode_workspace_bytes(...) bytes (256-byte
  *              aligned).  Rows with a single partition bypass the merge.
- *   flags      ADR_KERNEL_* in bits 0..3, optionally | ADR_PARTIALS_ONLY; other
- *              bits must be 0.
+ *   flags      ADR_KERNEL_* in bits 0..3, optionally | ADR_PARTIALS_ONLY |
+ *              ADR_SINGLE_PARTITION_ITEMS; other bits must be 0.
  *
  * Page ids are clamped into [0,num_pages) before use; table entries past
  * ceil(seq_len/page_size) are never dereferenced.  Results are bit-identical

@@ -14,6 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libadr.so")
 ADR_BF16, ADR_FP8_E4M3, ADR_F32 = 0, 1, 2
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_MFMA_GRID = 0, 1, 2, 3
 PARTIALS_ONLY = 16
+SINGLE_PARTITION_ITEMS = 32
 
 EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention", "adr_decode_step",
            "adr_decode_merge", "adr_lse_merge", "adr_probe_stream_read", "adr_probe_copy",

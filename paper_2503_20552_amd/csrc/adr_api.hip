@@ -184,7 +184,7 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
         return ADR_ERR_UNSUPPORTED;
     if (partition_tokens < 0 || partition_tokens % cache->page_size != 0)
         return ADR_ERR_SHAPE;
-    if (flags & ~(0xFu | ADR_PARTIALS_ONLY))
+    if (flags & ~(0xFu | ADR_PARTIALS_ONLY | ADR_SINGLE_PARTITION_ITEMS))
         return ADR_ERR_UNSUPPORTED;
     const int G = Hq / cache->Hkv;
     const int d = cache->d;
@@ -267,6 +267,7 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
     p.max_seq_len = max_seq_len;
     p.out_f32 = out_dtype == ADR_F32;
     p.scale_log2e = scale * adr::kLog2e;
+    p.coalesce = !(flags & ADR_SINGLE_PARTITION_ITEMS);
 
     // The new token goes in first: the append kernel, with the token index taken from seq_lens.
     if (nt) {

@@ -40,6 +40,7 @@ struct DecodeParams {
     int max_parts;        // partitions per request the grid was sized for (>= 1)
     int max_seq_len;
     int out_f32;          // 1: out is fp32, 0: bf16
+    int coalesce;         // the resident kernel may take runs of partitions as one item
     float scale_log2e;    // softmax scale * log2(e): scores are kept in base 2
 };
 

@@ -12,7 +12,10 @@
 //    arrays in LDS (full partitions per row, ragged last partitions per row);
 //    ticket t is decoded by binary search.  Tickets enumerate all full
 //    partitions first and the ragged ones last, so the work handed out at the
-//    very end is the small pieces.
+//    very end is the small pieces.  When a pass has tens of thousands of
+//    partitions, an item is a run of two or four neighbouring partitions of a
+//    row: what an item costs besides its pages (records, staging, combining) is
+//    paid that much less often.
 //  * Items are announced through a small queue of records in LDS.  The ticket of
 //    item k+3 is drawn at the start of item k by wave k mod 4, which decodes and
 //    publishes it when it has finished its share of item k; every wave picks a
@@ -60,6 +63,8 @@ constexpr int kQueue = 8;          // item records kept in LDS (power of two)
 constexpr int kSpinLimit = 1 << 24; // polls of an LDS word before a wait is declared failed (seconds: an
                                     // unsplit row of millions of tokens keeps a wave busy for tens of ms)
 constexpr int kSpinLimitAfterFault = 64; // ... once a wait of this workgroup has failed
+constexpr int kCoalesceItems = 8192;     // items (of the caller's partition size) per doubling of the item size:
+                                         // measured neutral below about 16K items, -5 to -10 % at 40K
 
 // Geometry of one ring stage: K tile, V tile, then (fp8) the two scales, each
 // in a 256-byte slot of its own (a 4-byte direct-to-LDS load covers 64 x 4 bytes).
@@ -135,10 +140,13 @@ __device__ __forceinline__ int find_row(const int *pref, int B, int u)
     return block * 8 + __popcll(__ballot(below2)) - 1;
 }
 
-__device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamParams &sp, int ticket)
+// cshift: tickets enumerate runs of 1 << cshift partitions (see the kernel's set-up); it.part
+// counts such runs, it.n_parts stays the row's number of partitions as the caller defined them.
+__device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamParams &sp, int ticket, int cshift)
 {
     Item it;
     const int Hkv = sp.d.Hkv, B = sp.d.B;
+    const int pt = sp.pt << cshift;
     // everything below is the same in all lanes; say so, to keep it in scalar registers
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     const int total_full = __builtin_amdgcn_readfirstlane(sh.total[0]);
@@ -153,7 +161,7 @@ __device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamPara
         if (unit < total_full) {
             b = find_row(sh.pref_full, B, unit);
             it.part = unit - sh.pref_full[b];
-            t1 = (it.part + 1) * sp.pt;
+            t1 = (it.part + 1) * pt;
         } else {
             b = find_row(sh.pref_rag, B, unit - total_full);
             it.part = sh.pref_full[b + 1] - sh.pref_full[b];
@@ -505,39 +513,19 @@ void decode_stream_kernel(const StreamParams sp)
                      : "memory");
 
     // ---- partitions per row: exclusive prefix sums over the rows, four rows per thread
+    int cshift = 0;
     {
-        int f[4], g[4], sf = 0, sg = 0;
-        int given[4]; // read without a condition (a row past the end re-reads the last one), so that
-                      // the four reads are in flight together instead of one after the other
+        int len4[4]; // this thread's rows; read without a condition (a row past the end re-reads the
+                     // last one), so that the four reads are in flight together
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            given[i] = p.seq_lens[min(tid * 4 + i, B - 1)];
+            len4[i] = p.seq_lens[min(tid * 4 + i, B - 1)];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = tid * 4 + i;
-            int L = 0;
-            f[i] = g[i] = 0;
-            if (row < B) {
-                L = max(min(given[i], p.max_seq_len), 0);
-                sh.len[row] = L;
-                f[i] = L / sp.pt;
-                g[i] = (L % sp.pt != 0 || L == 0) ? 1 : 0; // an empty row still owns one (empty) item
-            }
-            sf += f[i];
-            sg += g[i];
-        }
-        int xf = sf, xg = sg; // inclusive scan over the lanes of the wave
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int yf = __shfl_up(xf, off), yg = __shfl_up(xg, off);
-            if (lane >= off) {
-                xf += yf;
-                xg += yg;
-            }
-        }
-        if (lane == 63) {
-            sh.wave_tot[0][wave] = xf;
-            sh.wave_tot[1][wave] = xg;
+            len4[i] = row < B ? max(min(len4[i], p.max_seq_len), 0) : -1;
+            if (row < B)
+                sh.len[row] = len4[i];
         }
         if (tid < kQueue)
             sh.rec[tid].seq = -1;
@@ -546,33 +534,75 @@ void decode_stream_kernel(const StreamParams sp)
             sh.arrive[0] = sh.arrive[1] = 0;
             sh.failed = 0;
         }
-        __syncthreads();
-        int bf = 0, bg = 0, tf = 0, tg = 0;
+        // items of `pt` tokens: full ones per row, and one ragged (or empty) last one where there is one
+        auto scan_rows = [&](int pt) {
+            int f[4], g[4], sf = 0, sg = 0;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            if (w < wave) {
-                bf += sh.wave_tot[0][w];
-                bg += sh.wave_tot[1][w];
+            for (int i = 0; i < 4; ++i) {
+                const int L = len4[i];
+                f[i] = L >= 0 ? L / pt : 0;
+                g[i] = L >= 0 && (L % pt != 0 || L == 0) ? 1 : 0; // an empty row still owns one (empty) item
+                sf += f[i];
+                sg += g[i];
             }
-            tf += sh.wave_tot[0][w];
-            tg += sh.wave_tot[1][w];
-        }
-        int ef = bf + xf - sf, eg = bg + xg - sg;
+            int xf = sf, xg = sg; // inclusive scan over the lanes of the wave
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = tid * 4 + i;
-            if (row < B) {
-                sh.pref_full[row] = ef;
-                sh.pref_rag[row] = eg;
+            for (int off = 1; off < 64; off <<= 1) {
+                const int yf = __shfl_up(xf, off), yg = __shfl_up(xg, off);
+                if (lane >= off) {
+                    xf += yf;
+                    xg += yg;
+                }
             }
-            ef += f[i];
-            eg += g[i];
+            if (lane == 63) {
+                sh.wave_tot[0][wave] = xf;
+                sh.wave_tot[1][wave] = xg;
+            }
+            __syncthreads();
+            int bf = 0, bg = 0, tf = 0, tg = 0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                if (w < wave) {
+                    bf += sh.wave_tot[0][w];
+                    bg += sh.wave_tot[1][w];
+                }
+                tf += sh.wave_tot[0][w];
+                tg += sh.wave_tot[1][w];
+            }
+            int ef = bf + xf - sf, eg = bg + xg - sg;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = tid * 4 + i;
+                if (row < B) {
+                    sh.pref_full[row] = ef;
+                    sh.pref_rag[row] = eg;
+                }
+                ef += f[i];
+                eg += g[i];
+            }
+            if (tid == 0) {
+                sh.pref_full[B] = tf;
+                sh.pref_rag[B] = tg;
+                sh.total[0] = tf;
+                sh.total[1] = tg;
+            }
+            __syncthreads();
+        };
+        scan_rows(sp.pt);
+        // Many items: hand out runs of two or four partitions as one item.  What an item costs
+        // besides its pages (records, staging, combining) is then paid half or a quarter as
+        // often, and there are still enough items to balance the workgroups.  The run's result
+        // goes to its first partition's place and the others are marked empty, which the merge
+        // skips.  The threshold counts items, not workgroups, so the choice (and with it the
+        // order of the floating-point sums) depends on the inputs alone.
+        if (p.coalesce && p.partition_tokens > 0 && sp.pt <= (1 << 24)) {
+            const int64_t items = ((int64_t)sh.total[0] + sh.total[1]) * Hkv;
+            cshift = items >= 4 * kCoalesceItems ? 2 : items >= 2 * kCoalesceItems ? 1 : 0;
+            cshift = __builtin_amdgcn_readfirstlane(cshift);
+            if (cshift)
+                scan_rows(sp.pt << cshift);
         }
         if (tid == 0) {
-            sh.pref_full[B] = tf;
-            sh.pref_rag[B] = tg;
-            sh.total[0] = tf;
-            sh.total[1] = tg;
             asm volatile("s_waitcnt vmcnt(0)" : "+v"(first_ticket)::"memory");
             sh.first[0] = (int)first_ticket;
             sh.first[1] = (int)first_ticket + 1;
@@ -580,7 +610,7 @@ void decode_stream_kernel(const StreamParams sp)
         }
         __syncthreads();
         if (wave < 3)
-            publish(sh.rec[wave], decode_ticket(sh, sp, sh.first[wave]), wave);
+            publish(sh.rec[wave], decode_ticket(sh, sp, sh.first[wave], cshift), wave);
         __syncthreads();
     }
 
@@ -624,7 +654,7 @@ void decode_stream_kernel(const StreamParams sp)
         (void *)(FP8 ? (const void *)p.k_scale : (const void *)kc), 0, scale_range, 0x00020000);
     const __amdgpu_buffer_rsrc_t vs_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(FP8 ? (const void *)p.v_scale : (const void *)kc), 0, scale_range, 0x00020000);
-    const int pages_per_part = sp.pt / kPageSize; // 2^26 when the pass is not split (part is 0 then)
+    const int pages_per_part = (sp.pt << cshift) / kPageSize; // 2^26 when the pass is not split (part is 0 then)
     // "Page" below is a 16-token tile of the pool; a cache page is 1 << tsh of them (the
     // instantiations with a fixed ring depth serve 16-token pages only).
     const int tsh = STAGES > 0 ? 0 : p.page_shift;
@@ -809,7 +839,7 @@ void decode_stream_kernel(const StreamParams sp)
         asm volatile("" : "+v"(next_ticket)::"memory"); // the ticket is read after the wait, not before
         if (drawer)
             publish(sh.rec[(k + 3) & (kQueue - 1)],
-                    decode_ticket(sh, sp, (int)__builtin_amdgcn_readfirstlane(next_ticket)), k + 3);
+                    decode_ticket(sh, sp, (int)__builtin_amdgcn_readfirstlane(next_ticket), cshift), k + 3);
 
         if (C.valid) {
             // ---- deliver this wave's share; the last wave to arrive combines the four
@@ -893,12 +923,20 @@ void decode_stream_kernel(const StreamParams sp)
                             if (p.lse && c4[t] == 0)
                                 p.lse[(int64_t)C.b * p.Hq + h] = lse;
                         } else {
-                            const int64_t row = ((int64_t)C.b * p.max_parts + C.part) * p.Hq + h;
+                            const int64_t row = ((int64_t)C.b * p.max_parts + (C.part << cshift)) * p.Hq + h;
                             *(f32x4 *)(p.part_o + row * D + c4[t]) = o;
                             if (c4[t] == 0)
                                 p.part_lse[row] = lse;
                         }
                     }
+                }
+                if (cshift && C.n_parts > 1) {
+                    // the other partitions of the run carry no mass: lse = -inf, payload never read
+                    const int slot = (C.part << cshift) + 1;
+                    const int n = (min((C.part + 1) << cshift, C.n_parts) - slot) * G;
+                    if (lane < n)
+                        p.part_lse[((int64_t)C.b * p.max_parts + slot + lane / G) * p.Hq + C.kvh * G + lane % G] =
+                            -INFINITY;
                 }
                 if (lane == 0) {
                     flag_write(&sh.arrive[buf], 0);

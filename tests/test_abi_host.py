@@ -65,7 +65,7 @@ NULL, SHAPE, UNSUP, WORK = 1, 2, 3, 4
     (dict(partition_tokens=-16), SHAPE),
     (dict(B=-1), SHAPE),
     (dict(out_dtype=adr.ADR_FP8_E4M3), UNSUP),
-    (dict(flags=4), UNSUP), (dict(flags=32), UNSUP),
+    (dict(flags=4), UNSUP), (dict(flags=64), UNSUP),
     (dict(Hq=2 * 32, q_row_stride=64 * 128), UNSUP),   # G = 32
     (dict(partition_tokens=16), WORK),         # split needs a workspace
     (dict(partition_tokens=16, workspace=FAKE, workspace_bytes=16), WORK),

@@ -213,6 +213,38 @@ def test_split_equals_unsplit_within_rounding():
         assert (lw - ls).abs().max().item() < 2e-5
 
 
+@pytest.mark.parametrize("lo,hi,run", [(100, 165, 2), (225, 320, 4)])
+@pytest.mark.parametrize("fp8", [False, True])
+def test_many_items_are_handed_out_in_runs_of_partitions(lo, hi, run, fp8):
+    """With tens of thousands of items the resident kernel takes runs of two or four partitions as one
+    item and marks the other partitions of a run empty for the merge.  Lengths cross every boundary of
+    partitions and runs; the merged result must be the oracle's, and the same as with the runs off."""
+    rng = np.random.default_rng(77 + run)
+    lens = rng.integers(lo, hi, size=512)
+    lens[:12] = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 192, 0]
+    items = int(np.sum(np.maximum(-(-(lens + 1) // 32), 1))) * 8
+    assert items >= 8192 * run and (run == 4 or items < 8192 * 4), items   # the kernel's own thresholds
+    b = small_case(61, 32, 8, 128, lens)
+    say("runs of %d partitions, %d items, fp8=%s" % (run, items, fp8))
+    if fp8:
+        k8, ks = W.quantize_pool_fp8(b.k_cache, b.used)
+        v8, vs = W.quantize_pool_fp8(b.v_cache, b.used)
+        args = (dev(b.q), dev(k8), dev(v8), dev(b.block_table), dev(b.seq_lens), b.wl.scale)
+        kw = dict(partition_tokens=32, k_scale=dev(ks), v_scale=dev(vs))
+        ref, ref_lse, _ = oracle.decode_attention(W.bits(b.q), W.bits(k8), W.bits(v8), b.block_table, b.seq_lens,
+                                                  b.wl.scale, k_scale=W.bits(ks), v_scale=W.bits(vs))
+    else:
+        args = (dev(b.q), dev(b.k_cache), dev(b.v_cache), dev(b.block_table), dev(b.seq_lens), b.wl.scale)
+        kw = dict(partition_tokens=32)
+        ref, ref_lse = oracle_attention(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.wl.scale)
+    out, lse = gpu_attention(*args, flags=adr.KERNEL_MFMA, **kw)
+    assert compare(out, lse, ref, ref_lse, what="runs of %d" % run)[0] <= ATOL
+    single, lse1 = gpu_attention(*args, flags=adr.KERNEL_MFMA | adr.SINGLE_PARTITION_ITEMS, **kw)
+    assert compare(single, lse1, ref, ref_lse, what="single-partition items")[0] <= ATOL
+    assert not torch.equal(out, single)          # the two really took different routes
+    assert (out - single).abs().max().item() < 2e-5
+
+
 @pytest.mark.parametrize("kernel", ["valu", "mfma", "grid"])
 def test_one_long_unsplit_row_among_short_ones(kernel):
     """A single pass over a 40 000-token row (2 500 pages through one item) next to tiny rows."""

@@ -16,10 +16,11 @@ import pytest
 
 KW = 4; KQ = 8
 
-def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed):
+def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshift=0):
     rnd = random.Random(seed)
     B = len(seq_lens)
-    pt = pt_arg if pt_arg > 0 else (1 << 30)
+    pt_given = pt_arg if pt_arg > 0 else (1 << 30)
+    pt = pt_given << (cshift if pt_arg > 0 else 0)   # items are runs of 1 << cshift partitions
     L = np.clip(seq_lens, 0, max_seq_len)
     f = L // pt; g = ((L % pt != 0) | (L == 0)).astype(int)
     pref_full = np.concatenate([[0], np.cumsum(f)]); pref_rag = np.concatenate([[0], np.cumsum(g)])
@@ -45,7 +46,7 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed):
             else:
                 b = find_row(pref_rag, unit - tf); it["part"] = int(pref_full[b + 1] - pref_full[b]); t1 = int(L[b])
             it["b"] = b; it["t1"] = t1
-            it["n_parts"] = (int(L[b]) - 1) // pt + 1 if L[b] > 0 else 1
+            it["n_parts"] = (int(L[b]) - 1) // pt_given + 1 if L[b] > 0 else 1   # as the caller counts them
         return it
     consumed = {}      # (b, kvh, page_index) -> count
     combined = {}      # (b, kvh, part) -> count
@@ -171,7 +172,7 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed):
             for h in range(Hkv):
                 exp_pages[(b, h, p_)] = 1
     assert consumed == exp_pages, ("coverage", len(consumed), len(exp_pages))
-    exp_items = {}
+    exp_items = {}   # one combined result per run of partitions
     for b in range(B):
         npart = (int(L[b]) - 1) // pt + 1 if L[b] > 0 else 1
         for p_ in range(npart):
@@ -195,13 +196,14 @@ for _trial in range(24):
     else:
         _lens = _rng.integers(500, 520, size=_B)
     CASES.append((_trial, _lens.astype(np.int32), int(_rng.choice([1, 2, 8])), int(_rng.choice([0, 64, 512])),
-                  int(_rng.choice([2, 3, 4, 6])), int(_rng.choice([1, 2])), int(_rng.choice([1, 2, 5, 16]))))
+                  int(_rng.choice([2, 3, 4, 6])), int(_rng.choice([1, 2])), int(_rng.choice([1, 2, 5, 16])),
+                  _trial % 3))
 
 
-@pytest.mark.parametrize("trial,lens,Hkv,pt,S,NB,n_wg", CASES, ids=[str(c[0]) for c in CASES])
-def test_protocol_covers_every_page_once_and_terminates(trial, lens, Hkv, pt, S, NB, n_wg):
+@pytest.mark.parametrize("trial,lens,Hkv,pt,S,NB,n_wg,cshift", CASES, ids=[str(c[0]) for c in CASES])
+def test_protocol_covers_every_page_once_and_terminates(trial, lens, Hkv, pt, S, NB, n_wg, cshift):
     rng = np.random.default_rng(100 + trial)
     maxp = max(1, (int(lens.max()) + 15) // 16)
     table = rng.integers(0, 10000, size=(len(lens), maxp)).astype(np.int32)
-    stats = run(lens, table, Hkv, pt, int(lens.max()), n_wg, S, NB, trial)
+    stats = run(lens, table, Hkv, pt, int(lens.max()), n_wg, S, NB, trial, cshift)
     assert stats["pairs"] + stats["singles"] > 0 or int(lens.max()) == 0
