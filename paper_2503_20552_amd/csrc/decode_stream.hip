@@ -34,8 +34,11 @@
 //    pending inside the page loop and the compiler adds no waits there.
 //  * The per-wave results of an item meet in a staging buffer (two buffers,
 //    used alternately).  Each wave adds itself to the buffer's arrival counter;
-//    the wave that arrives last combines the four results, writes the output and
-//    hands the buffer back.  Nobody else waits.
+//    the waves take turns to combine: the one whose turn it is waits for the
+//    counter to reach four, combines the four results, writes the output and
+//    hands the buffer back.  Nobody else waits.  (Leaving it to the last wave to
+//    arrive would load every item's extra work on the wave the others are already
+//    waiting for.)
 //
 // fp8 cache: a page of one kv-head is half the bytes (two loads per tile instead
 // of four), and two more 4-byte direct-to-LDS loads bring the page's K and V
@@ -842,7 +845,7 @@ void decode_stream_kernel(const StreamParams sp)
                     decode_ticket(sh, sp, (int)__builtin_amdgcn_readfirstlane(next_ticket), cshift), k + 3);
 
         if (C.valid) {
-            // ---- deliver this wave's share; the last wave to arrive combines the four
+            // ---- deliver this wave's share; one wave, in turn, combines the four
             const int buf = sp.nb == 2 ? (k & 1) : 0;
             const int use = sp.nb == 2 ? (k >> 1) : k;
             poll_equal(&sh.gen[buf], use, &sh.failed, sp.faults); // the buffer's previous item has been combined
@@ -861,13 +864,14 @@ void decode_stream_kernel(const StreamParams sp)
                     *(f32x4 *)(so + g * D + 8 * r + 4) = f32x4{st.o[4][i], st.o[5][i], st.o[6][i], st.o[7][i]};
                 }
             }
-            int arrived = 0;
             lds_order();
             if (lane == 0)
-                arrived = flag_add(&sh.arrive[buf], 1);
-            arrived = __builtin_amdgcn_readfirstlane(arrived);
+                flag_add(&sh.arrive[buf], 1);
             lds_order();
-            if (arrived == kWaves - 1) {
+            // The combining falls to the waves in turn, not to the last one to arrive: that one is
+            // the wave the others end up waiting for, and it would carry every item's extra work.
+            // The wave whose turn it is waits until all four have delivered.
+            if (((k + 2) & (kWaves - 1)) == wave && poll_equal(&sh.arrive[buf], kWaves, &sh.failed, sp.faults)) {
                 // Two output quads per lane and round; all LDS reads of a round are issued
                 // before anything is computed, so the round costs one LDS latency, not ten.
                 const float *sbase = staging + buf * kWaves * (G * D);
@@ -948,13 +952,12 @@ void decode_stream_kernel(const StreamParams sp)
             const int buf = sp.nb == 2 ? (k & 1) : 0;
             const int use = sp.nb == 2 ? (k >> 1) : k;
             poll_equal(&sh.gen[buf], use, &sh.failed, sp.faults);
-            int arrived = 0;
             lds_order();
             if (lane == 0)
-                arrived = flag_add(&sh.arrive[buf], 1);
-            arrived = __builtin_amdgcn_readfirstlane(arrived);
+                flag_add(&sh.arrive[buf], 1);
             lds_order();
-            if (arrived == kWaves - 1 && lane == 0) {
+            if (((k + 2) & (kWaves - 1)) == wave && poll_equal(&sh.arrive[buf], kWaves, &sh.failed, sp.faults) &&
+                lane == 0) {
                 flag_write(&sh.arrive[buf], 0);
                 flag_write(&sh.gen[buf], use + 1);
             }

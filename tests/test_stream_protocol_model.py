@@ -127,8 +127,11 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshi
             if C["valid"]:
                 assert sh["stage_owner"][buf][wave] is None, "staging overwritten"
                 sh["stage_owner"][buf][wave] = k
-            arrived = sh["arrive"][buf]; sh["arrive"][buf] += 1
-            if arrived == KW - 1:
+            sh["arrive"][buf] += 1
+            if (k + 2) % KW == wave:   # the combining goes round the waves; it waits for all four deliveries
+                while sh["arrive"][buf] != KW:
+                    stats["polls"] += 1
+                    yield
                 if C["valid"]:
                     assert all(o == k for o in sh["stage_owner"][buf]), ("combine mix", sh["stage_owner"][buf], k)
                     key = (C["b"], C["kvh"], C["part"]); combined[key] = combined.get(key, 0) + 1
