@@ -209,14 +209,11 @@ __device__ __forceinline__ void flag_write(int *word, int value)
     asm volatile("ds_write_b32 %0, %1" ::"v"(lds_address(word)), "v"(value) : "memory");
 }
 
-__device__ __forceinline__ int flag_add(int *word, int value)
+// Add without waiting for anything: the LDS takes it in this wave's program order, behind
+// the writes issued before it.
+__device__ __forceinline__ void flag_add_async(int *word, int value)
 {
-    int old;
-    asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&v"(old)
-                 : "v"(lds_address(word)), "v"(value)
-                 : "memory");
-    return old;
+    asm volatile("ds_add_u32 %0, %1" ::"v"(lds_address(word)), "v"(value) : "memory");
 }
 
 // Poll an LDS word until it holds `want`.  Returns false (and counts a fault)
@@ -254,17 +251,30 @@ __device__ __forceinline__ void publish(Rec &rec, const Item &it, int seq)
     }
 }
 
-__device__ __forceinline__ Item fetch(Rec &rec, int seq, int *failed, unsigned long long *faults)
+// `also`, when given, is another LDS word read in the same round trip (every dependent LDS access
+// costs a wave a few hundred cycles here); its value comes back in *also_value.
+__device__ __forceinline__ Item fetch(Rec &rec, int seq, int *failed, unsigned long long *faults,
+                                      const int *also = nullptr, int *also_value = nullptr)
 {
     // The record is 32 bytes; its stamp is written last, so a copy whose stamp is the
     // wanted one is whole.  The common case is one round trip.
     Item it;
     typedef int i32x4 __attribute__((ext_vector_type(4)));
     i32x4 lo, hi;
-    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&v"(lo), "=&v"(hi)
-                 : "v"(lds_address(&rec))
-                 : "memory");
+    if (also) {
+        int extra;
+        asm volatile("ds_read_b128 %0, %3\n\tds_read_b128 %1, %3 offset:16\n\tds_read_b32 %2, %4\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&v"(lo), "=&v"(hi), "=&v"(extra)
+                     : "v"(lds_address(&rec)), "v"(lds_address(also))
+                     : "memory");
+        *also_value = __builtin_amdgcn_readfirstlane(extra);
+    } else {
+        asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(lo), "=&v"(hi)
+                     : "v"(lds_address(&rec))
+                     : "memory");
+    }
     bool ok = __builtin_amdgcn_readfirstlane(lo[0]) == seq;
     if (!ok) {
         ok = poll_equal(&rec.seq, seq, failed, faults);
@@ -844,11 +854,19 @@ void decode_stream_kernel(const StreamParams sp)
             publish(sh.rec[(k + 3) & (kQueue - 1)],
                     decode_ticket(sh, sp, (int)__builtin_amdgcn_readfirstlane(next_ticket), cshift), k + 3);
 
+        // ---- the record of the item after next and the state of this item's staging buffer, in one
+        // LDS round trip (and ahead of the delivery, so that the item's last matrix instructions
+        // drain behind it)
+        const int buf = sp.nb == 2 ? (k & 1) : 0;
+        const int use = sp.nb == 2 ? (k >> 1) : k;
+        int gen_seen = 0;
+        const Item after_next =
+            fetch(sh.rec[(k + 2) & (kQueue - 1)], k + 2, &sh.failed, sp.faults, &sh.gen[buf], &gen_seen);
+        if (gen_seen != use)
+            poll_equal(&sh.gen[buf], use, &sh.failed, sp.faults); // the buffer's previous item has been combined
+
         if (C.valid) {
             // ---- deliver this wave's share; one wave, in turn, combines the four
-            const int buf = sp.nb == 2 ? (k & 1) : 0;
-            const int use = sp.nb == 2 ? (k >> 1) : k;
-            poll_equal(&sh.gen[buf], use, &sh.failed, sp.faults); // the buffer's previous item has been combined
             float l = st.l;
             l = sum_across_rows(l);
             float *so = staging + (buf * kWaves + wave) * (G * D); // [G][D]
@@ -866,7 +884,7 @@ void decode_stream_kernel(const StreamParams sp)
             }
             lds_order();
             if (lane == 0)
-                flag_add(&sh.arrive[buf], 1);
+                flag_add_async(&sh.arrive[buf], 1); // behind the writes above, in the LDS's order
             lds_order();
             // The combining falls to the waves in turn, not to the last one to arrive: that one is
             // the wave the others end up waiting for, and it would carry every item's extra work.
@@ -949,12 +967,9 @@ void decode_stream_kernel(const StreamParams sp)
             }
         } else {
             // an item past the end still occupies its turn of the staging buffers
-            const int buf = sp.nb == 2 ? (k & 1) : 0;
-            const int use = sp.nb == 2 ? (k >> 1) : k;
-            poll_equal(&sh.gen[buf], use, &sh.failed, sp.faults);
             lds_order();
             if (lane == 0)
-                flag_add(&sh.arrive[buf], 1);
+                flag_add_async(&sh.arrive[buf], 1);
             lds_order();
             if (((k + 2) & (kWaves - 1)) == wave && poll_equal(&sh.arrive[buf], kWaves, &sh.failed, sp.faults) &&
                 lane == 0) {
@@ -965,7 +980,7 @@ void decode_stream_kernel(const StreamParams sp)
 
         // ---- next item becomes current
         C = N;
-        N = fetch(sh.rec[(k + 2) & (kQueue - 1)], k + 2, &sh.failed, sp.faults);
+        N = after_next;
         // The cursor is always inside the item that has just become current (issuing
         // the last page of an item moves it on, and so does an item without pages).
         ld_in_next = 0;
