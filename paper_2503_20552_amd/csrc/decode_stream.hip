@@ -128,49 +128,53 @@ struct alignas(16) Shared {
     int len[kMaxStreamB];
 };
 
-// largest b < B with pref[b] <= u  (pref is an exclusive prefix sum, pref[0] = 0 <= u; B <= 512).
+// largest b < B with pref[b] <= u  (pref is an exclusive prefix sum, pref[0] = 0 <= u; B <= 512);
+// *at_row receives pref[b].
 // Called by a whole wave: sixty-four lanes probe every eighth entry, eight lanes the eight
 // entries of the block found, and the counts of the two ballots give the row -- two LDS round
-// trips instead of the nine of a binary search.
-__device__ __forceinline__ int find_row(const int *pref, int B, int u)
+// trips instead of the nine of a binary search (each costs the wave a few hundred cycles).
+__device__ __forceinline__ int find_row(const int *pref, int B, int u, int *at_row)
 {
     const int lane = threadIdx.x & 63;
     const int coarse = lane * 8;
     const bool below = coarse < B && pref[coarse] <= u;
     const int block = __popcll(__ballot(below)) - 1;
     const int fine = block * 8 + (lane & 7);
-    const bool below2 = lane < 8 && fine < B && pref[fine] <= u;
-    return block * 8 + __popcll(__ballot(below2)) - 1;
+    const int value = lane < 8 && fine < B ? pref[fine] : 0x7fffffff;
+    const int hits = __popcll(__ballot(value <= u));
+    *at_row = __builtin_amdgcn_readlane(value, hits - 1);
+    return block * 8 + hits - 1;
 }
 
 // cshift: tickets enumerate runs of 1 << cshift partitions (see the kernel's set-up); it.part
 // counts such runs, it.n_parts stays the row's number of partitions as the caller defined them.
-__device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamParams &sp, int ticket, int cshift)
+// total_full / total_rag: the item counts the scan left in sh.total, kept in registers.
+__device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamParams &sp, int ticket, int cshift,
+                                              int total_full, int total_rag)
 {
     Item it;
     const int Hkv = sp.d.Hkv, B = sp.d.B;
     const int pt = sp.pt << cshift;
     // everything below is the same in all lanes; say so, to keep it in scalar registers
     ticket = __builtin_amdgcn_readfirstlane(ticket);
-    const int total_full = __builtin_amdgcn_readfirstlane(sh.total[0]);
-    const int total_rag = __builtin_amdgcn_readfirstlane(sh.total[1]);
     it.valid = (unsigned)ticket < (unsigned)((total_full + total_rag) * Hkv);
     it.b = it.kvh = it.part = it.t1 = 0;
     it.n_parts = 1;
     if (it.valid) {
         const int unit = ticket / Hkv;
         it.kvh = ticket - unit * Hkv;
-        int b, t1;
+        int b, at_row, L, t1;
         if (unit < total_full) {
-            b = find_row(sh.pref_full, B, unit);
-            it.part = unit - sh.pref_full[b];
+            b = find_row(sh.pref_full, B, unit, &at_row);
+            L = sh.len[b];
+            it.part = unit - at_row;
             t1 = (it.part + 1) * pt;
         } else {
-            b = find_row(sh.pref_rag, B, unit - total_full);
-            it.part = sh.pref_full[b + 1] - sh.pref_full[b];
-            t1 = sh.len[b];
+            b = find_row(sh.pref_rag, B, unit - total_full, &at_row);
+            L = sh.len[b];
+            it.part = L / pt; // the full items of the row come before its ragged one
+            t1 = L;
         }
-        const int L = sh.len[b];
         it.b = __builtin_amdgcn_readfirstlane(b);
         it.part = __builtin_amdgcn_readfirstlane(it.part);
         it.kvh = __builtin_amdgcn_readfirstlane(it.kvh);
@@ -526,7 +530,7 @@ void decode_stream_kernel(const StreamParams sp)
                      : "memory");
 
     // ---- partitions per row: exclusive prefix sums over the rows, four rows per thread
-    int cshift = 0;
+    int cshift = 0, total_full = 0, total_rag = 0;
     {
         int len4[4]; // this thread's rows; read without a condition (a row past the end re-reads the
                      // last one), so that the four reads are in flight together
@@ -615,6 +619,8 @@ void decode_stream_kernel(const StreamParams sp)
             if (cshift)
                 scan_rows(sp.pt << cshift);
         }
+        total_full = __builtin_amdgcn_readfirstlane(sh.total[0]);
+        total_rag = __builtin_amdgcn_readfirstlane(sh.total[1]);
         if (tid == 0) {
             asm volatile("s_waitcnt vmcnt(0)" : "+v"(first_ticket)::"memory");
             sh.first[0] = (int)first_ticket;
@@ -623,7 +629,7 @@ void decode_stream_kernel(const StreamParams sp)
         }
         __syncthreads();
         if (wave < 3)
-            publish(sh.rec[wave], decode_ticket(sh, sp, sh.first[wave], cshift), wave);
+            publish(sh.rec[wave], decode_ticket(sh, sp, sh.first[wave], cshift, total_full, total_rag), wave);
         __syncthreads();
     }
 
@@ -852,7 +858,9 @@ void decode_stream_kernel(const StreamParams sp)
         asm volatile("" : "+v"(next_ticket)::"memory"); // the ticket is read after the wait, not before
         if (drawer)
             publish(sh.rec[(k + 3) & (kQueue - 1)],
-                    decode_ticket(sh, sp, (int)__builtin_amdgcn_readfirstlane(next_ticket), cshift), k + 3);
+                    decode_ticket(sh, sp, (int)__builtin_amdgcn_readfirstlane(next_ticket), cshift, total_full,
+                                  total_rag),
+                    k + 3);
 
         // ---- the record of the item after next and the state of this item's staging buffer, in one
         // LDS round trip (and ahead of the delivery, so that the item's last matrix instructions
