@@ -49,4 +49,5 @@ def test_pins_fail_on_a_planted_mistake(name, tmp_path):
     run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
                           "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
     assert run.returncode != 0, "every pin passed with the mistake '%s' planted in the oracle" % name
-    assert "failed" in run.stdout or "error" in run.stdout.lower(), run.stdout[-400:]
+    # a pin that failed, or a child that died outright (a mistake in an index can read outside the arrays)
+    assert run.returncode < 0 or "failed" in run.stdout or "error" in run.stdout.lower(), run.stdout[-400:]
