@@ -34,11 +34,12 @@
 //    pending inside the page loop and the compiler adds no waits there.
 //  * The per-wave results of an item meet in a staging buffer (two buffers,
 //    used alternately).  Each wave adds itself to the buffer's arrival counter;
-//    the waves take turns to combine: the one whose turn it is waits for the
-//    counter to reach four, combines the four results, writes the output and
-//    hands the buffer back.  Nobody else waits.  (Leaving it to the last wave to
-//    arrive would load every item's extra work on the wave the others are already
-//    waiting for.)
+//    the waves take turns to combine, one item late: at the end of item k the
+//    wave whose turn it is combines item k - 1 out of the other buffer (checking
+//    that its counter has reached four, which it almost always has), writes the
+//    output and hands that buffer back.  Nobody falls in step with the slowest
+//    wave.  (Leaving the combine to the last wave to arrive would load every
+//    item's extra work on the wave the others are already waiting for.)
 //
 // fp8 cache: a page of one kv-head is half the bytes (two loads per tile instead
 // of four), and two more 4-byte direct-to-LDS loads bring the page's K and V
@@ -759,6 +760,8 @@ void decode_stream_kernel(const StreamParams sp)
 
     uint32_t next_ticket = 0;
     int invalid_run = 0;
+    Item P = C; // the item before the current one (combined one item late); not read before it is one
+    P.valid = 0;
     // Tickets are drawn by four different waves at their own pace, so a ticket past
     // the end can precede a valid one in the queue; each wave's own draws are in
     // order, so four invalid records in a row mean the work is finished.
@@ -873,8 +876,8 @@ void decode_stream_kernel(const StreamParams sp)
         if (gen_seen != use)
             poll_equal(&sh.gen[buf], use, &sh.failed, sp.faults); // the buffer's previous item has been combined
 
+        // ---- deliver this wave's share (an item past the end still takes its turn of the buffers)
         if (C.valid) {
-            // ---- deliver this wave's share; one wave, in turn, combines the four
             float l = st.l;
             l = sum_across_rows(l);
             float *so = staging + (buf * kWaves + wave) * (G * D); // [G][D]
@@ -890,101 +893,102 @@ void decode_stream_kernel(const StreamParams sp)
                     *(f32x4 *)(so + g * D + 8 * r + 4) = f32x4{st.o[4][i], st.o[5][i], st.o[6][i], st.o[7][i]};
                 }
             }
-            lds_order();
-            if (lane == 0)
-                flag_add_async(&sh.arrive[buf], 1); // behind the writes above, in the LDS's order
-            lds_order();
-            // The combining falls to the waves in turn, not to the last one to arrive: that one is
-            // the wave the others end up waiting for, and it would carry every item's extra work.
-            // The wave whose turn it is waits until all four have delivered.
-            if (((k + 2) & (kWaves - 1)) == wave && poll_equal(&sh.arrive[buf], kWaves, &sh.failed, sp.faults)) {
-                // Two output quads per lane and round; all LDS reads of a round are issued
-                // before anything is computed, so the round costs one LDS latency, not ten.
-                const float *sbase = staging + buf * kWaves * (G * D);
-                const int quads = G * (D / 4);
-                typedef float f32x2 __attribute__((ext_vector_type(2)));
-                for (int base = 0; base < quads; base += 128) {
-                    bool ok[2];
-                    int g[2], c4[2];
-                    f32x2 ml[2][kWaves];
-                    f32x4 x[2][kWaves];
+        }
+        lds_order();
+        if (lane == 0)
+            flag_add_async(&sh.arrive[buf], 1); // behind the writes above, in the LDS's order
+        lds_order();
+
+        // ---- combine.  The waves take turns (leaving it to the last one to arrive would load every
+        // item's extra work on the wave the others are already waiting for).  With two staging
+        // buffers the turn is one item late: at the end of item k the wave combines item k - 1,
+        // which the other three have almost always delivered by then, so that nobody has to fall
+        // in step with the slowest wave; with one buffer it combines item k and waits for them.
+        const int late = sp.nb == 2 ? 1 : 0;
+        if (((k + 2) & (kWaves - 1)) == wave && k >= late) {
+            const Item &Q = late ? P : C;
+            const int qbuf = late ? ((k - 1) & 1) : 0;
+            const int quse = late ? ((k - 1) >> 1) : k;
+            if (poll_equal(&sh.arrive[qbuf], kWaves, &sh.failed, sp.faults)) {
+                if (Q.valid) {
+                    // Two output quads per lane and round; all LDS reads of a round are issued
+                    // before anything is computed, so the round costs one LDS latency, not ten.
+                    const float *sbase = staging + qbuf * kWaves * (G * D);
+                    const int quads = G * (D / 4);
+                    typedef float f32x2 __attribute__((ext_vector_type(2)));
+                    for (int base = 0; base < quads; base += 128) {
+                        bool ok[2];
+                        int g[2], c4[2];
+                        f32x2 ml[2][kWaves];
+                        f32x4 x[2][kWaves];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const int idx = base + 64 * t + lane;
-                        ok[t] = idx < quads;
-                        g[t] = ok[t] ? idx / (D / 4) : 0;
-                        c4[t] = (idx & (D / 4 - 1)) * 4;
+                        for (int t = 0; t < 2; ++t) {
+                            const int idx = base + 64 * t + lane;
+                            ok[t] = idx < quads;
+                            g[t] = ok[t] ? idx / (D / 4) : 0;
+                            c4[t] = (idx & (D / 4 - 1)) * 4;
 #pragma unroll
-                        for (int w = 0; w < kWaves; ++w) {
-                            ml[t][w] = *(const f32x2 *)&sh.ml[buf][w][g[t]][0];
-                            x[t][w] = *(const f32x4 *)(sbase + w * (G * D) + g[t] * D + c4[t]);
-                        }
-                    }
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        if (!ok[t])
-                            continue;
-                        float M = kNegBig;
-#pragma unroll
-                        for (int w = 0; w < kWaves; ++w)
-                            M = fmaxf(M, ml[t][w][0]);
-                        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-                        float den = 0.f;
-#pragma unroll
-                        for (int w = 0; w < kWaves; ++w) {
-                            const float f = fast_exp2(ml[t][w][0] - M);
-                            acc += f * x[t][w];
-                            den += f * ml[t][w][1];
-                        }
-                        const float inv = den > 0.f ? 1.f / den : 0.f;
-                        const f32x4 o = acc * inv;
-                        const float lse = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
-                        const int h = C.kvh * G + g[t];
-                        if (C.n_parts == 1) {
-                            const int64_t off = ((int64_t)C.b * p.Hq + h) * D + c4[t];
-                            if (p.out_f32) {
-                                *(f32x4 *)((float *)p.out + off) = o;
-                            } else {
-                                u32x2 packed;
-                                packed[0] = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
-                                packed[1] = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
-                                *(u32x2 *)((uint16_t *)p.out + off) = packed;
+                            for (int w = 0; w < kWaves; ++w) {
+                                ml[t][w] = *(const f32x2 *)&sh.ml[qbuf][w][g[t]][0];
+                                x[t][w] = *(const f32x4 *)(sbase + w * (G * D) + g[t] * D + c4[t]);
                             }
-                            if (p.lse && c4[t] == 0)
-                                p.lse[(int64_t)C.b * p.Hq + h] = lse;
-                        } else {
-                            const int64_t row = ((int64_t)C.b * p.max_parts + (C.part << cshift)) * p.Hq + h;
-                            *(f32x4 *)(p.part_o + row * D + c4[t]) = o;
-                            if (c4[t] == 0)
-                                p.part_lse[row] = lse;
+                        }
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) {
+                            if (!ok[t])
+                                continue;
+                            float M = kNegBig;
+#pragma unroll
+                            for (int w = 0; w < kWaves; ++w)
+                                M = fmaxf(M, ml[t][w][0]);
+                            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                            float den = 0.f;
+#pragma unroll
+                            for (int w = 0; w < kWaves; ++w) {
+                                const float f = fast_exp2(ml[t][w][0] - M);
+                                acc += f * x[t][w];
+                                den += f * ml[t][w][1];
+                            }
+                            const float inv = den > 0.f ? 1.f / den : 0.f;
+                            const f32x4 o = acc * inv;
+                            const float lse = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
+                            const int h = Q.kvh * G + g[t];
+                            if (Q.n_parts == 1) {
+                                const int64_t off = ((int64_t)Q.b * p.Hq + h) * D + c4[t];
+                                if (p.out_f32) {
+                                    *(f32x4 *)((float *)p.out + off) = o;
+                                } else {
+                                    u32x2 packed;
+                                    packed[0] = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
+                                    packed[1] = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
+                                    *(u32x2 *)((uint16_t *)p.out + off) = packed;
+                                }
+                                if (p.lse && c4[t] == 0)
+                                    p.lse[(int64_t)Q.b * p.Hq + h] = lse;
+                            } else {
+                                const int64_t row = ((int64_t)Q.b * p.max_parts + (Q.part << cshift)) * p.Hq + h;
+                                *(f32x4 *)(p.part_o + row * D + c4[t]) = o;
+                                if (c4[t] == 0)
+                                    p.part_lse[row] = lse;
+                            }
                         }
                     }
+                    if (cshift && Q.n_parts > 1) {
+                        // the other partitions of the run carry no mass: lse = -inf, payload never read
+                        const int slot = (Q.part << cshift) + 1;
+                        const int n = (min((Q.part + 1) << cshift, Q.n_parts) - slot) * G;
+                        if (lane < n)
+                            p.part_lse[((int64_t)Q.b * p.max_parts + slot + lane / G) * p.Hq + Q.kvh * G + lane % G] =
+                                -INFINITY;
+                    }
                 }
-                if (cshift && C.n_parts > 1) {
-                    // the other partitions of the run carry no mass: lse = -inf, payload never read
-                    const int slot = (C.part << cshift) + 1;
-                    const int n = (min((C.part + 1) << cshift, C.n_parts) - slot) * G;
-                    if (lane < n)
-                        p.part_lse[((int64_t)C.b * p.max_parts + slot + lane / G) * p.Hq + C.kvh * G + lane % G] =
-                            -INFINITY;
+                if (lane == 0) { // hand the buffer back
+                    flag_write(&sh.arrive[qbuf], 0);
+                    flag_write(&sh.gen[qbuf], quse + 1);
                 }
-                if (lane == 0) {
-                    flag_write(&sh.arrive[buf], 0);
-                    flag_write(&sh.gen[buf], use + 1);
-                }
-            }
-        } else {
-            // an item past the end still occupies its turn of the staging buffers
-            lds_order();
-            if (lane == 0)
-                flag_add_async(&sh.arrive[buf], 1);
-            lds_order();
-            if (((k + 2) & (kWaves - 1)) == wave && poll_equal(&sh.arrive[buf], kWaves, &sh.failed, sp.faults) &&
-                lane == 0) {
-                flag_write(&sh.arrive[buf], 0);
-                flag_write(&sh.gen[buf], use + 1);
             }
         }
+        P = C;
 
         // ---- next item becomes current
         C = N;

@@ -86,6 +86,7 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshi
         settle()
         invalid_run = 0
         k = 0
+        P = dict(valid=0)
         while True:
             invalid_run = 0 if C["valid"] else invalid_run + 1
             if invalid_run == KW:
@@ -128,15 +129,23 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshi
                 assert sh["stage_owner"][buf][wave] is None, "staging overwritten"
                 sh["stage_owner"][buf][wave] = k
             sh["arrive"][buf] += 1
-            if (k + 2) % KW == wave:   # the combining goes round the waves; it waits for all four deliveries
-                while sh["arrive"][buf] != KW:
+            # The combining goes round the waves.  With two staging buffers it is one item late: at
+            # the end of item k the wave whose turn it is combines item k - 1, which the others have
+            # most likely delivered already; with one buffer it combines item k and waits for them.
+            late = 1 if NB == 2 else 0
+            if (k + 2) % KW == wave and k >= late:
+                q = k - late
+                qbuf = (q % 2) if NB == 2 else 0
+                Q = P if late else C
+                while sh["arrive"][qbuf] != KW:
                     stats["polls"] += 1
                     yield
-                if C["valid"]:
-                    assert all(o == k for o in sh["stage_owner"][buf]), ("combine mix", sh["stage_owner"][buf], k)
-                    key = (C["b"], C["kvh"], C["part"]); combined[key] = combined.get(key, 0) + 1
-                    sh["stage_owner"][buf] = [None] * KW
-                sh["arrive"][buf] = 0; sh["gen"][buf] = use + 1
+                if Q["valid"]:
+                    assert all(o == q for o in sh["stage_owner"][qbuf]), ("combine mix", sh["stage_owner"][qbuf], q)
+                    key = (Q["b"], Q["kvh"], Q["part"]); combined[key] = combined.get(key, 0) + 1
+                    sh["stage_owner"][qbuf] = [None] * KW
+                sh["arrive"][qbuf] = 0; sh["gen"][qbuf] = ((q // 2) if NB == 2 else q) + 1
+            P = C
             yield
             C = N
             N = yield from fetch(k + 2)
