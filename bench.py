@@ -195,9 +195,9 @@ def main():
     bytes_per_launch = kv_bytes / (layers * K)
     achieved = bytes_per_launch / (attn_ms.mean() * 1e-3) / 1e9
     G = wl.Hq // wl.Hkv
-    if flags == adr.KERNEL_VALU or wl.d != 128 or (fp8 and wl.B > 512):
+    if flags == adr.KERNEL_VALU or wl.d != 128:
         kernel_name = "decode_valu_kernel"
-    elif wl.B <= 512 and (fp8 or flags == adr.KERNEL_MFMA or (part > 0 and st["max_len"] > part and G <= 4)):
+    elif fp8 or flags == adr.KERNEL_MFMA or (part > 0 and st["max_len"] > part and G <= 4):
         kernel_name = "decode_stream_kernel"
     else:
         kernel_name = "decode_mfma_kernel"

@@ -59,8 +59,8 @@ enum {
     ADR_KERNEL_AUTO = 0, /* the library picks per shape */
     ADR_KERNEL_VALU = 1, /* vector-ALU dot products, any supported shape */
     ADR_KERNEL_MFMA = 2, /* matrix-core QK^T and PV (d = 128): resident workgroups pulling
-                            (request, partition, kv-head) items when B <= 512, else (bf16
-                            cache only) the one-workgroup-per-item form below */
+                            (request, partition, kv-head) items; batches of more than 512 rows
+                            go out as one launch per 512 rows */
     ADR_KERNEL_MFMA_GRID = 3, /* matrix cores, one workgroup per (request, partition, kv-head);
                                  bf16 cache only */
     /* Bit 4: run the partition pass only and leave the merge to a later

@@ -1028,7 +1028,8 @@ std::atomic<unsigned> g_next_slot{0}, g_next_recorded_slot{0};
 
 bool decode_stream_supports(int d, int G, int B)
 {
-    return d == D && G >= 1 && G <= 16 && B <= kMaxStreamB;
+    (void)B; // any batch: more than kMaxStreamB rows go out as several launches
+    return d == D && G >= 1 && G <= 16;
 }
 
 namespace {
@@ -1071,10 +1072,38 @@ hipError_t device_info(int *dev_out)
 }
 } // namespace
 
+namespace {
+hipError_t launch_rows(const DecodeParams &p, int d, bool fp8, hipStream_t stream);
+}
+
+// The kernel's length scan holds kMaxStreamB rows; a larger batch goes out as several launches
+// over consecutive row ranges (each a full pass over its rows, into its own part of every
+// per-row array).
 hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStream_t stream)
 {
     if (!decode_stream_supports(d, p.G, p.B))
         return hipErrorInvalidValue;
+    const size_t out_elem = p.out_f32 ? 4 : 2;
+    for (int b0 = 0; b0 < p.B; b0 += kMaxStreamB) {
+        DecodeParams c = p;
+        c.B = std::min(kMaxStreamB, p.B - b0);
+        c.q = p.q + (int64_t)b0 * p.q_row_stride;
+        c.block_table = p.block_table + (int64_t)b0 * p.max_pages;
+        c.seq_lens = p.seq_lens + b0;
+        c.out = (char *)p.out + (size_t)b0 * p.Hq * D * out_elem;
+        c.lse = p.lse ? p.lse + (int64_t)b0 * p.Hq : nullptr;
+        c.part_o = p.part_o ? p.part_o + (int64_t)b0 * p.max_parts * p.Hq * D : nullptr;
+        c.part_lse = p.part_lse ? p.part_lse + (int64_t)b0 * p.max_parts * p.Hq : nullptr;
+        const hipError_t e = launch_rows(c, d, fp8, stream);
+        if (e != hipSuccess)
+            return e;
+    }
+    return hipSuccess;
+}
+
+namespace {
+hipError_t launch_rows(const DecodeParams &p, int d, bool fp8, hipStream_t stream)
+{
     int dev = 0;
     hipError_t e = device_info(&dev);
     if (e != hipSuccess)
@@ -1157,6 +1186,7 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
         decode_stream_kernel<false, 0><<<blocks, kThreads, lds, stream>>>(sp);
     return hipGetLastError();
 }
+} // namespace
 
 // Number of bounded waits that expired in any launch on the current device since
 // the library was loaded (0 unless the kernel's hand-shakes are broken).  Synchronises.

@@ -245,6 +245,31 @@ def test_many_items_are_handed_out_in_runs_of_partitions(lo, hi, run, fp8):
     assert (out - single).abs().max().item() < 2e-5
 
 
+@pytest.mark.parametrize("fp8", [False, True])
+def test_batches_of_more_than_512_rows_on_the_resident_kernel(fp8):
+    """The resident kernel's length scan holds 512 rows; 1 100 rows go out as three launches."""
+    rng = np.random.default_rng(91)
+    lens = rng.integers(0, 90, size=1100)
+    lens[[0, 511, 512, 1023, 1024, 1099]] = [200, 1, 130, 64, 0, 77]
+    b = small_case(67, 8, 2, 128, lens)
+    say("1100 rows on the resident kernel, fp8=%s" % fp8)
+    if fp8:
+        k8, ks = W.quantize_pool_fp8(b.k_cache, b.used)
+        v8, vs = W.quantize_pool_fp8(b.v_cache, b.used)
+        args = (dev(b.q), dev(k8), dev(v8), dev(b.block_table), dev(b.seq_lens), b.wl.scale)
+        kw = dict(k_scale=dev(ks), v_scale=dev(vs))
+        ref, ref_lse, _ = oracle.decode_attention(W.bits(b.q), W.bits(k8), W.bits(v8), b.block_table, b.seq_lens,
+                                                  b.wl.scale, k_scale=W.bits(ks), v_scale=W.bits(vs))
+    else:
+        args = (dev(b.q), dev(b.k_cache), dev(b.v_cache), dev(b.block_table), dev(b.seq_lens), b.wl.scale)
+        kw = {}
+        ref, ref_lse = oracle_attention(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.wl.scale)
+    for part in (0, 64):
+        for out_dtype in (torch.float32, torch.bfloat16):
+            out, lse = gpu_attention(*args, partition_tokens=part, flags=adr.KERNEL_MFMA, out_dtype=out_dtype, **kw)
+            compare(out, lse, ref, ref_lse, what="1100 rows part=%d %s" % (part, out_dtype))
+
+
 @pytest.mark.parametrize("kernel", ["valu", "mfma", "grid"])
 def test_one_long_unsplit_row_among_short_ones(kernel):
     """A single pass over a 40 000-token row (2 500 pages through one item) next to tiny rows."""
