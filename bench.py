@@ -38,6 +38,8 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     (3, "decode_stream_kernel"): 2344268188,   # profiles/decode_stream_kernel_workload3.md
     (3, "decode_mfma_kernel"): 2338000000,     # profiles/decode_mfma_kernel_workload3.md
+    (5, "decode_stream_kernel"): 10527967410,  # profiles/decode_stream_kernel_workloads2_5_bf16.md
+    (2, "decode_stream_kernel"): 1447074690,   # profiles/decode_stream_kernel_workloads2_5_bf16.md
 }
 
 
