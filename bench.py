@@ -40,6 +40,7 @@ MEASURED_TRAFFIC_BYTES = {
     (3, "decode_mfma_kernel"): 2338000000,     # profiles/decode_mfma_kernel_workload3.md
     (5, "decode_stream_kernel"): 10527967410,  # profiles/decode_stream_kernel_workloads2_5_bf16.md
     (2, "decode_stream_kernel"): 1447074690,   # profiles/decode_stream_kernel_workloads2_5_bf16.md
+    (5, "decode_stream_kernel", "fp8"): 5453852358,  # profiles/decode_stream_kernel_workload5_fp8.md
 }
 
 
@@ -203,7 +204,7 @@ def main():
         kernel_name = "decode_stream_kernel"
     else:
         kernel_name = "decode_mfma_kernel"
-    traffic = MEASURED_TRAFFIC_BYTES.get((wl.ident, kernel_name)) if not fp8 else None
+    traffic = MEASURED_TRAFFIC_BYTES.get((wl.ident, kernel_name, "fp8") if fp8 else (wl.ident, kernel_name))
     roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "avg_kernel_ms": round(float(attn_ms.mean()), 5),
