@@ -200,7 +200,7 @@ def main():
     G = wl.Hq // wl.Hkv
     if flags == adr.KERNEL_VALU or wl.d != 128:
         kernel_name = "decode_valu_kernel"
-    elif fp8 or flags == adr.KERNEL_MFMA or (part > 0 and st["max_len"] > part and G <= 4):
+    elif fp8 or flags == adr.KERNEL_MFMA or (part > 0 and st["max_len"] > part and (G <= 4 or wl.B * wl.Hkv >= 2048)):
         kernel_name = "decode_stream_kernel"
     else:
         kernel_name = "decode_mfma_kernel"

@@ -207,12 +207,14 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
         else
             return ADR_ERR_UNSUPPORTED;
     } else if (want == ADR_KERNEL_AUTO) {
-        // Measured on MI355X: the resident-workgroup kernel wins on split passes of
-        // small groups (many equal items); whole-row items and the wide-group shape
-        // run faster one workgroup per item.
+        // Measured on MI355X: the resident-workgroup kernel wins on split passes with many items
+        // (groups of up to four heads always; wider groups from 2048 (request, kv-head) pairs
+        // on: +11 % at 256 requests x 8 kv-heads, G = 8; about even at a quarter of that);
+        // whole-row items and small passes of wide groups run faster one workgroup per item.
         const bool splits = partition_tokens > 0 && max_seq_len > partition_tokens;
+        const bool many = (int64_t)B * cache->Hkv >= 2048;
         // An fp8 cache has the resident-workgroup kernel and the vector-ALU one only.
-        if ((fp8 || (splits && G <= 4)) && adr::decode_stream_supports(d, G, B))
+        if ((fp8 || (splits && (G <= 4 || many))) && adr::decode_stream_supports(d, G, B))
             kernel = MFMA_STREAM;
         else if (!fp8 && adr::decode_mfma_supports(d, G))
             kernel = MFMA_GRID;
