@@ -27,15 +27,35 @@ BF16 = 0
 FP8_E4M3 = 1
 
 
+PORTABLE_FLAGS = ["-O2"]
+# The flags the CPU baseline is quoted with.  -ffp-contract=off keeps every product and sum
+# rounded as written, so both builds give the same bits; the code is built on the machine
+# that runs it, never shipped.
+NATIVE_FLAGS = ["-O3", "-march=native", "-ffp-contract=off"]
+
+
 def build(force: bool = False) -> str:
-    """Compile adr_oracle.c with gcc (OpenMP) into libadr_oracle.so."""
+    """Compile adr_oracle.c with gcc (OpenMP) into libadr_oracle.so (portable code: the file may
+    be built on one machine and loaded on another)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+            ["gcc", *PORTABLE_FLAGS, "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
              "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
+
+
+def use_native_build(directory: str) -> str:
+    """Build the same source for this machine's own CPU into `directory` and make this process
+    use that build from now on (the benchmark's CPU-baseline leg calls it on the box it times)."""
+    global _lib
+    so = os.path.join(directory, "libadr_oracle_native.so")
+    subprocess.check_call(["gcc", *NATIVE_FLAGS, "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall",
+                           "-Wextra", "-o", so, _SRC, "-lm"])
+    _lib = None
+    _load(so)
+    return " ".join(["gcc", *NATIVE_FLAGS, "-fopenmp"])
 
 
 class _Cache(ctypes.Structure):
@@ -48,12 +68,12 @@ class _Cache(ctypes.Structure):
 _lib = None
 
 
-def _load():
+def _load(path=None):
     global _lib
     if _lib is None:
-        # ADR_ORACLE_MUTANT names a deliberately broken build of the C file; only the test that
-        # checks that the pins notice such builds sets it.
-        lib = ctypes.CDLL(os.environ.get("ADR_ORACLE_MUTANT") or build())
+        # ADR_ORACLE_MUTANT names another build of the C file (a deliberately broken one, or one
+        # with sanitizers); only the tests that check the pins against such builds set it.
+        lib = ctypes.CDLL(path or os.environ.get("ADR_ORACLE_MUTANT") or build())
         lib.oracle_fp8_e4m3_decode.restype = ctypes.c_double
         lib.oracle_fp8_e4m3_decode.argtypes = [ctypes.c_uint8]
         lib.oracle_fp8_e4m3_encode.restype = ctypes.c_uint8
