@@ -9,16 +9,21 @@ pass and the log-sum-exp merge (--separate-append: adr_kv_append, then
 adr_decode_attention).  Sequences grow by one token per step.
 Prints ONE JSON line: whole-job attended-KV bandwidth (algorithmic bytes of K
 and V attended per second, inputs resident in HBM), the roofline of the
-dominant kernel from HIP events on the launch stream, and the fp64 oracle timed
-on the host cores as a baseline.
+dominant kernel from HIP events on the launch stream, the fp64 oracle timed
+on the host cores as a baseline, and (object "corun") the same attention steps
+next to a compute-bound neighbour: a bf16 8192^3 matrix product on a second
+stream, with the compute units shared freely and split by queue masks, for the
+matrix-core kernel and for the vector-ALU kernel.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import math
 import os
 import sys
+import tempfile
 import time
 
 import numpy as np
@@ -34,14 +39,24 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of this command (see profiles/), scaled by the same counters'
-# reading on adr_probe_copy.  None until such a run has been recorded.
+# reading on adr_probe_copy.  A profiler run cannot happen inside this script, so the
+# figure is carried here together with the hash of the kernel sources it was taken
+# with (`python bench.py --csrc-hash` prints the current one): with other sources the
+# line reports traffic null rather than a stale number.
 MEASURED_TRAFFIC_BYTES = {
-    (3, "decode_stream_kernel"): 2344268188,   # profiles/decode_stream_kernel_workload3.md
-    (3, "decode_mfma_kernel"): 2338000000,     # profiles/decode_mfma_kernel_workload3.md
-    (5, "decode_stream_kernel"): 10527967410,  # profiles/decode_stream_kernel_workloads2_5_bf16.md
-    (2, "decode_stream_kernel"): 1447074690,   # profiles/decode_stream_kernel_workloads2_5_bf16.md
-    (5, "decode_stream_kernel", "fp8"): 5453852358,  # profiles/decode_stream_kernel_workload5_fp8.md
+    # (workload, kernel[, "fp8"]): (bytes per launch, hash of csrc/ at the time, summary under profiles/)
 }
+
+
+def csrc_hash() -> str:
+    """Hash of the library's kernel sources (what a traffic figure was measured with)."""
+    d = os.path.join(ROOT, "paper_2503_20552_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def log(msg):
@@ -94,6 +109,9 @@ def main():
     ap.add_argument("--separate-append", action="store_true",
                     help="adr_kv_append then adr_decode_attention per layer instead of one adr_decode_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-corun", action="store_true", help="leave the colocation object out of the line")
+    ap.add_argument("--corun-steps", type=int, default=3, help="attention steps per colocation measurement")
+    ap.add_argument("--csrc-hash", action="store_true", help="print the hash of the kernel sources and exit")
     ap.add_argument("--corun-gemm", action="store_true",
                     help="colocation measurement: the attention steps on one stream while bf16 8192^3 matrix "
                          "products run on another; prints its own JSON line (alone and contended rates)")
@@ -107,6 +125,9 @@ def main():
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch adr_probe_copy once on 1 GiB (calibrates profiler byte counters)")
     args = ap.parse_args()
+    if args.csrc_hash:
+        print(csrc_hash())
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "--gpus %d is not supported, use --gpus 1" % args.gpus, file=sys.stderr)
@@ -139,24 +160,27 @@ def main():
     # K and V of one token in one layer (+ an fp8 page's two scales per kv-head, shared by its 16 tokens)
     bytes_per_token = 2 * wl.Hkv * wl.d * elem + (2 * wl.Hkv * 4 / wl.page_size if fp8 else 0)
 
-    def one_step(s, events=None, pos=None, seq=None):
+    def one_step(s, events=None, pos=None, seq=None, kernel_flags=None):
         if pos is None:
             pos, seq = st["positions"][s], st["seq_lens"][s]
+        kf = flags if kernel_flags is None else kernel_flags
         for li, cache in enumerate(st["caches"]):
             if events is None and not args.separate_append:
                 # append and attention in one call (the token index is seq - 1 = pos)
                 adr.adr_decode_step(out, st["q"], st["k_new"], st["v_new"], cache, st["table"], seq, wl.scale,
-                                    st["max_len"], part, ws, None, flags)
+                                    st["max_len"], part, ws, None, kf)
                 continue
             adr.adr_kv_append(cache, st["k_new"], st["v_new"], st["table"], pos)
             if events is None:
                 adr.adr_decode_attention(out, st["q"], cache, st["table"], seq, wl.scale, st["max_len"],
-                                         part, ws, None, flags)
+                                         part, ws, None, kf)
             else:   # the same three kernels in the same order, with events around the partition pass and the merge
+                # (the workspace's control area is clear: every earlier call left it so, which saves the
+                # attention call its clearing kernel, as the append does inside adr_decode_step)
                 e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
                 e0.record()
                 adr.adr_decode_attention(out, st["q"], cache, st["table"], seq, wl.scale, st["max_len"],
-                                         part, ws, None, flags | adr.PARTIALS_ONLY)
+                                         part, ws, None, kf | adr.PARTIALS_ONLY | adr.WORKSPACE_READY)
                 e1.record()
                 adr.adr_decode_merge(out, seq, st["max_len"], part, ws)
                 e2.record()
@@ -197,22 +221,27 @@ def main():
     merge_ms = np.array([e1.elapsed_time(e2) for _, e1, e2 in events])
     bytes_per_launch = kv_bytes / (layers * K)
     achieved = bytes_per_launch / (attn_ms.mean() * 1e-3) / 1e9
-    G = wl.Hq // wl.Hkv
-    if flags == adr.KERNEL_VALU or wl.d != 128:
-        kernel_name = "decode_valu_kernel"
-    elif fp8 or flags == adr.KERNEL_MFMA or (part > 0 and st["max_len"] > part and (G <= 4 or wl.B * wl.Hkv >= 2048)):
-        kernel_name = "decode_stream_kernel"
-    else:
-        kernel_name = "decode_mfma_kernel"
-    traffic = MEASURED_TRAFFIC_BYTES.get((wl.ident, kernel_name, "fp8") if fp8 else (wl.ident, kernel_name))
+    # the library says which kernel it runs for this shape
+    kernel_name = adr.adr_kernel_name(adr.adr_decode_kernel_choice(st["caches"][0], wl.B, wl.Hq, st["max_len"],
+                                                                   part, flags))
+    traffic, traffic_source = None, None
+    default_shape = layers == wl.layers and part == wl.partition_tokens
+    entry = MEASURED_TRAFFIC_BYTES.get((wl.ident, kernel_name, "fp8") if fp8 else (wl.ident, kernel_name))
+    if entry and default_shape and entry[1] == csrc_hash():
+        traffic, traffic_source = entry[0], entry[2]
     roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_source": traffic_source,
                 "avg_kernel_ms": round(float(attn_ms.mean()), 5),
                 "median_kernel_ms": round(float(np.median(attn_ms)), 5), "launches": int(len(attn_ms)),
                 "algorithmic_bytes_per_launch": int(bytes_per_launch),
                 "merge_avg_ms": round(float(merge_ms.mean()), 5)}
     log("partition pass %.4f ms avg (min %.4f, max %.4f), merge %.4f ms avg" % (
         attn_ms.mean(), attn_ms.min(), attn_ms.max(), merge_ms.mean()))
+
+    corun = None
+    if not args.no_corun and not fp8 and wl.d == 128:
+        corun = corun_summary(args, wl, st, one_step, bytes_per_token, layers)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -224,8 +253,8 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(elapsed / K * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.cache_dtype, "data": "synthetic",
-        "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d page=16 %s cache, %d resident layers, partition %d + LSE "
-                               "merge, lengths %s" % (wl.name, wl.B, wl.Hq, wl.Hkv, wl.d,
+        "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d page=%d %s cache, %d resident layers, partition %d + LSE "
+                               "merge, lengths %s" % (wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, wl.page_size,
                                                       "fp8-e4m3" if fp8 else "bf16", layers, part, wl.lengths),
                    "kernel": args.kernel, "layers": layers, "partition_tokens": part,
                    "cache_dtype": args.cache_dtype},
@@ -233,9 +262,127 @@ def main():
         "attended_tokens_per_s": round(attended_tokens / elapsed, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "corun": corun,
     }
     print(json.dumps(line), flush=True)
     return 0
+
+
+class Neighbour:
+    """The compute-bound neighbour of Sec. 3.3's colocation: bf16 n x n x n products, back to back."""
+
+    def __init__(self, wl, n=8192, dev="cuda:0"):
+        self.n = n
+        self.a = W.randn_bf16((n, n), wl.seed + 50, dev)
+        self.b = W.randn_bf16((n, n), wl.seed + 51, dev)
+        self.c = torch.empty((n, n), dtype=torch.bfloat16, device=dev)
+        self.flop = 2.0 * n ** 3
+
+    def product(self):
+        torch.matmul(self.a, self.b, out=self.c)
+
+    def alone_ms(self, stream, reps=8):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(stream):
+            self.product()
+            e0.record()
+            for _ in range(reps):
+                self.product()
+            e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def tflops(self, ms):
+        return round(self.flop / ms / 1e9, 1)
+
+
+def side_by_side(attention_pass, attn_stream, nb, nb_stream, attn_alone_ms, gemm_alone_ms):
+    """The attention pass on one stream while products run on the other from before its start to after
+    its end.  Returns (attention ms, mean ms of the products that ran wholly inside the attention's
+    window, how many those were)."""
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+    # enough products to cover the attention pass even if it slows down fourfold
+    n_gemm = max(4, int(math.ceil(4.0 * attn_alone_ms / gemm_alone_ms)) + 2)
+    marks = [ev() for _ in range(n_gemm + 1)]
+    c0, c1 = ev(), ev()
+    with torch.cuda.stream(nb_stream):
+        marks[0].record()
+        for i in range(n_gemm):
+            nb.product()
+            marks[i + 1].record()
+    with torch.cuda.stream(attn_stream):
+        c0.record(); attention_pass(); c1.record()
+    torch.cuda.synchronize()
+    inside = [marks[i].elapsed_time(marks[i + 1]) for i in range(n_gemm)
+              if c0.elapsed_time(marks[i]) >= 0 and marks[i + 1].elapsed_time(c1) >= 0]
+    return c0.elapsed_time(c1), (float(np.mean(inside)) if inside else None), len(inside)
+
+
+def corun_summary(args, wl, st, one_step, bytes_per_token, layers):
+    """The colocation half of the target (Sec. 3.3), short enough for the default run: the attention
+    steps alone and next to the neighbour, (i) on two plain streams and (ii) with the compute units
+    split by queue masks, each for the matrix-core kernel the library picks and for the vector-ALU
+    kernel (whose arithmetic does not compete for the matrix pipe the neighbour is using)."""
+    b = st["batch"]
+    Wm, K = args.warmup, args.corun_steps
+    steps = list(range(Wm, Wm + min(K, args.steps)))
+    tokens = [int(b.lens_before.sum()) + wl.B * (s + 1) for s in steps]
+    kv_bytes = layers * sum(tokens) * bytes_per_token
+    total_cus = torch.cuda.get_device_properties(0).multi_processor_count
+    nb = Neighbour(wl)
+    kernels = {"matrix_core": None}
+    G = wl.Hq // wl.Hkv
+    if G in (1, 2, 4, 8):
+        kernels["vector_alu"] = adr.KERNEL_VALU
+
+    def gbps(ms):
+        return round(kv_bytes / ms / 1e6, 1)
+
+    def measure(attn_stream, nb_stream):
+        row = {}
+        gemm_ms = nb.alone_ms(nb_stream)
+        row["gemm_alone_TFLOPs"] = nb.tflops(gemm_ms)
+        for name, kf in kernels.items():
+            def attention_pass():
+                for s in steps:
+                    one_step(s, kernel_flags=kf)
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(attn_stream):
+                attention_pass()                                     # warm-up on this stream
+                a0.record(); attention_pass(); a1.record()
+            torch.cuda.synchronize()
+            alone_ms = a0.elapsed_time(a1)
+            co_ms, gemm_co_ms, n_inside = side_by_side(attention_pass, attn_stream, nb, nb_stream, alone_ms, gemm_ms)
+            row[name] = {"attention_alone_GBps": gbps(alone_ms), "attention_contended_GBps": gbps(co_ms),
+                         "contended_pct_of_hbm_peak": round(100 * kv_bytes / co_ms / 1e6 / HBM_PEAK_GBS, 1),
+                         "gemm_contended_TFLOPs": nb.tflops(gemm_co_ms) if gemm_co_ms else None,
+                         "gemms_inside_attention_window": n_inside}
+        return row
+
+    for _ in range(3):
+        nb.product()
+    torch.cuda.synchronize()
+    res = {"neighbour": "bf16 %d^3 torch.matmul on a second stream, back to back" % nb.n,
+           "attention_steps_per_measurement": len(steps), "total_cus": total_cus}
+    res["plain_streams"] = measure(torch.cuda.Stream(), torch.cuda.Stream())        # default priority, both
+    res["cu_split"] = []
+    for n_attn in (192, 224):
+        if n_attn >= total_cus:
+            continue
+        ha = adr.adr_stream_create_cu_mask([i < n_attn for i in range(total_cus)])
+        hb = adr.adr_stream_create_cu_mask([i >= n_attn for i in range(total_cus)])
+        try:
+            row = {"attention_cus": n_attn, "gemm_cus": total_cus - n_attn}
+            row.update(measure(torch.cuda.ExternalStream(ha), torch.cuda.ExternalStream(hb)))
+            res["cu_split"].append(row)
+        finally:
+            torch.cuda.synchronize()
+            adr.adr_stream_destroy(ha)
+            adr.adr_stream_destroy(hb)
+        log("corun split %s" % json.dumps(row))
+    log("corun plain streams %s" % json.dumps(res["plain_streams"]))
+    return res
 
 
 def corun_gemm(args, wl, st, one_step, bytes_per_token, layers, part):
@@ -479,6 +626,11 @@ def cpu_baseline(wl, st, step, bytes_per_token):
     whole layers of the same workload at the first timed step's lengths, as many
     as give roughly 10-30 s of CPU work."""
     import oracle
+    try:    # the same source built for this machine's CPU (same bits; the flags the baseline is quoted with)
+        build = oracle.use_native_build(tempfile.mkdtemp(prefix="adr_oracle_"))
+    except Exception as e:  # no compiler on this box: the portable build that travelled with the tree
+        log("native oracle build failed (%s); timing the portable build" % e)
+        build = "gcc -O2 -fopenmp (portable build)"
     b = st["batch"]
     seq = st["seq_lens"][step].cpu().numpy()
     pairs_per_layer = int(seq.sum()) * wl.Hq                 # (token, q-head) dot products and V sums
@@ -502,6 +654,7 @@ def cpu_baseline(wl, st, step, bytes_per_token):
     return {"value": round(gbs, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
             "sample": "fp64 oracle over %d of %d layers, all %d requests (%d attended token-layers), %.2f s wall"
                       % (n_layers, len(st["caches"]), wl.B, tokens, dt),
+            "build": build,
             "attended_tokens_per_s": round(tokens / dt, 1)}
 
 

@@ -18,11 +18,14 @@
  *    Calls only enqueue kernels: no synchronisation, no allocation, no copies
  *    to the host, grids sized from host scalars only, so a call may be recorded
  *    into a HIP graph (Sec. 3.2.2 relies on replaying pre-launched kernels).
- *  - Concurrency: calls on different streams of one device may overlap, up to 128 attention
- *    launches in flight.  A launch recorded into a graph keeps a pair of device counters for all
- *    its replays (128 such launches can be alive): replays of one recorded graph must not overlap
- *    each other, and no more than 128 recorded attention launches should exist at a time if
- *    different graphs may run concurrently.
+ *  - Concurrency: calls on different streams of one device may overlap as long as they do not
+ *    share a workspace (two calls, or two replays of one recorded graph, that use one workspace
+ *    at the same time race on its contents).  The counters the attention kernels hand work out
+ *    with live in the workspace.  Only a call WITHOUT a workspace (an unsplit pass, workspace
+ *    NULL) falls back on a pool of 128 + 128 counter blocks inside the library (direct launches
+ *    and launches recorded into graphs); more than 128 such launches running at once, or 128
+ *    such recorded launches alive at once, would share blocks: give such calls the (small)
+ *    workspace adr_decode_workspace_bytes reports for partition_tokens = 0 instead.
  *  - Return value: ADR_OK or an error code.  Every host-checkable violation is
  *    reported BEFORE anything is launched and leaves all buffers untouched.
  *  - bf16 = upper 16 bits of IEEE binary32.  fp8 = OCP E4M3 (finite-only
@@ -57,7 +60,7 @@ typedef enum { ADR_BF16 = 0, ADR_FP8_E4M3 = 1, ADR_F32 = 2 } adr_dtype;
 /* Kernel choice for adr_decode_attention (bits 0..3 of `flags`). */
 enum {
     ADR_KERNEL_AUTO = 0, /* the library picks per shape */
-    ADR_KERNEL_VALU = 1, /* vector-ALU dot products, any supported shape */
+    ADR_KERNEL_VALU = 1, /* vector-ALU dot products: d in {64, 128}, G in {1, 2, 4, 8} */
     ADR_KERNEL_MFMA = 2, /* matrix-core QK^T and PV (d = 128): resident workgroups pulling
                             (request, partition, kv-head) items; batches of more than 512 rows
                             go out as one launch per 512 rows */
@@ -74,8 +77,23 @@ enum {
      * workspace at its first partition's place and the others are marked empty (lse = -inf),
      * which the merge skips.  The final result is the same up to the order of the
      * floating-point sums; the choice depends on the inputs alone. */
-    ADR_SINGLE_PARTITION_ITEMS = 32
+    ADR_SINGLE_PARTITION_ITEMS = 32,
+    /* The caller vouches that the workspace's control area (its last bytes, see
+     * adr_decode_workspace_bytes) is all zero: it was cleared by an earlier call on this workspace
+     * that has completed, and every call leaves it zero.  Saves adr_decode_attention the small
+     * kernel that clears it first (adr_decode_step never needs one).  On an area that is not zero
+     * the results are wrong or NaN. */
+    ADR_WORKSPACE_READY = 64,
+    /* Test aid: the resident matrix-core kernel's waits on other waves expire at once, as if its
+     * hand-shakes were broken.  Every kernel still runs to its end; the call's rows come back as
+     * NaN and adr_decode_read_status reports the expired waits. */
+    ADR_DEBUG_EXPIRE_WAITS = 128
 };
+/* Bits 16..27 of `flags`: size the resident kernel's grid for n compute units (1..4095) instead
+ * of asking the stream for its compute-unit mask.  Needed while a graph is being recorded for a
+ * masked stream: a recording stream cannot be asked, and the grid is then sized for the whole
+ * chip. */
+#define ADR_GRID_CUS(n) (((unsigned)(n) & 0xFFFu) << 16)
 
 /* The paged KV cache of ONE layer ("cache blocks", Sec. 3.2.1).  K and V are
  * separate arrays of identical shape [num_pages][page_size][Hkv][d],
@@ -112,8 +130,12 @@ int adr_kv_append(const adr_kv_cache *cache, const void *k_new, const void *v_ne
                   int64_t new_row_stride, const int32_t *block_table, int max_pages_per_req,
                   const int32_t *positions, int B, void *stream);
 
-/* Bytes of workspace adr_decode_attention needs for a split pass; 0 when
- * partition_tokens == 0.  Depends only on host scalars. */
+/* Bytes of workspace for a call of adr_decode_attention / adr_decode_step; depends only on host
+ * scalars (0 for sizes that are not positive).  The workspace holds the partitions' results of a
+ * split pass (nothing when partition_tokens == 0) and, in its last 256 * (1 + ceil(B / 512))
+ * bytes, the call's control area: a status block and the counters the resident kernel hands
+ * work out with.  A split pass needs the workspace; an unsplit one may do without (see
+ * "Concurrency" above).  The contents need no initialisation by the caller. */
 size_t adr_decode_workspace_bytes(int B, int Hq, int d, int max_seq_len, int partition_tokens);
 
 /*
@@ -155,7 +177,8 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
  * new token's K/V join the cache and the row attends over all its tokens, the new one included.
  * Same result, in `out`, `lse` and the cache, as
  *     adr_kv_append(cache, k_new, v_new, new_row_stride, block_table, max_pages_per_req, pos, B, stream)
- *     with pos[b] = min(max(seq_lens[b], 0), max_seq_len) - 1   (an empty row appends nothing),
+ *     with pos[b] = seq_lens[b] - 1, or -1 (append nothing) for an empty row and for a row with
+ *     seq_lens[b] > max_seq_len: such a row is attended up to the bound, where an older token sits,
  * followed by adr_decode_attention with the remaining arguments.
  *
  *   k_new, v_new  bf16 [B][Hkv][d], rows new_row_stride ELEMENTS apart (views into the grouped
@@ -178,9 +201,11 @@ int adr_decode_step(void *out, adr_dtype out_dtype, float *lse, const void *q, i
  * called with ADR_PARTIALS_ONLY: merges the partitions left in `workspace` into
  * out / lse for every row with more than one partition; other rows are left as
  * the first pass wrote them.  B, Hq, d, seq_lens, max_seq_len, partition_tokens
- * and the workspace must be those of the first pass.  A no-op (ADR_OK) when the
- * first pass did not split (max_seq_len <= partition_tokens or partition_tokens
- * == 0).
+ * and the workspace must be those of the first pass (partition_tokens is checked to be a
+ * multiple of 16 only; the first pass also held it to the cache's page size).  A no-op
+ * (ADR_OK) when the first pass did not split (max_seq_len <= partition_tokens or
+ * partition_tokens == 0).  If the first pass reported expired waits in the workspace's status
+ * block, every row of out / lse is set to NaN.
  */
 int adr_decode_merge(void *out, adr_dtype out_dtype, float *lse, const int32_t *seq_lens, int B,
                      int Hq, int d, int max_seq_len, int partition_tokens, const void *workspace,
@@ -260,7 +285,8 @@ int adr_scatter_rows(void *dst, int64_t dst_row_stride, int dst_rows, const void
  *   adr_offload_bound_comp  Eq. 2: (B_max - B_TPOT) / B_TPOT.  NaN when B_TPOT is not positive.
  *   adr_offload_bound       Eq. 3: the smaller of the two.
  * adr_need_offload, Algorithm 1 (Sec. 3.4.3): 1 when the new request's attention may be offloaded,
- *   0 when not, a negative status on a missing array.  `local` / `offloaded` are the decode
+ *   0 when not, and -ADR_ERR_NULL (a negative number: compare the result with 1, do not test it
+ *   as a boolean) on a missing array.  `local` / `offloaded` are the decode
  *   instance's running and offloaded requests; a request is its maximal and its current token
  *   count.  Read as printed: both conditions compare with strict "<", and the sum of the offloaded
  *   requests' maximal lengths, which the listing computes, enters neither condition.
@@ -284,11 +310,49 @@ int adr_graph_capacity(int n, int interval, int max_capacity);
 /*
  * Self-check of the resident-workgroup kernel (ADR_KERNEL_MFMA): its waves hand
  * work to each other through flags in on-chip memory, and every wait on such a
- * flag is bounded.  `*count` (a HOST pointer) receives the number of waits that
- * expired on the current device since the library was loaded; anything but 0
- * means results of that kernel cannot be trusted.  Synchronises the device.
+ * flag is bounded.  When one expires the kernel still runs to its end, but no row of
+ * that launch can be trusted: the launch's rows of out / lse (and its partitions' lse)
+ * are overwritten with NaN, the merge of a split pass sets every row of the call to NaN,
+ * and the expiry is counted in the workspace's status block and device-wide.
+ *   adr_decode_read_status  `*expired_waits` (HOST pointer) receives the status block's count
+ *       of the workspace (same B, Hq, d, max_seq_len, partition_tokens as the call): waits that
+ *       expired in calls on it since its control area was last cleared (every call clears it
+ *       unless it passes ADR_WORKSPACE_READY).  ADR_ERR_WORKSPACE when there is none.
+ *   adr_stream_fault_count  `*count` (HOST pointer) receives the number of waits that expired
+ *       on the current device since the library was loaded.
+ * Both synchronise the device.
  */
+int adr_decode_read_status(const void *workspace, size_t workspace_bytes, int B, int Hq, int d, int max_seq_len,
+                           int partition_tokens, uint32_t *expired_waits);
 int adr_stream_fault_count(uint64_t *count);
+
+/*
+ * Which kernel a pass of this shape and these flags runs on: ADR_KERNEL_VALU, ADR_KERNEL_MFMA
+ * (the resident matrix-core kernel) or ADR_KERNEL_MFMA_GRID, or minus an adr_status when the
+ * arguments are rejected.  The same decision adr_decode_attention takes.  adr_kernel_name gives
+ * the kernel's name as profilers show it (without template arguments); "" for other values.
+ */
+int adr_decode_kernel_choice(const adr_kv_cache *cache, int B, int Hq, int max_seq_len, int partition_tokens,
+                             unsigned flags);
+const char *adr_kernel_name(int kernel);
+
+/*
+ * Debug build of the library (compiled with -DADR_DEBUG_BOUNDS; `python -m
+ * paper_2503_20552_amd.build --debug` writes it next to the release library): table entries
+ * and append positions that fall outside the pool or the table are counted and the first one is
+ * kept.  The kernels treat them exactly as the release build does (page ids are clamped,
+ * out-of-range appends are skipped).  `*record` (HOST pointer) receives the device's record;
+ * reset != 0 clears it afterwards.  Synchronises.  The release build returns ADR_ERR_UNSUPPORTED.
+ */
+typedef struct adr_bounds_record {
+    uint32_t count; /* out-of-range reads / appends seen */
+    int32_t kind;   /* first one: 0 none, 1 attention read a page id outside [0, num_pages),
+                       2 append position outside the row's table, 3 append page id outside the pool */
+    int32_t row;    /* its request row */
+    int32_t index;  /* kind 1, 3: index into the row's table; kind 2: the position */
+    int32_t value;  /* kind 1, 3: the page id found; kind 2: tokens the table can describe */
+} adr_bounds_record;
+int adr_debug_bounds_status(adr_bounds_record *record, int reset);
 
 const char *adr_status_string(int status);
 int adr_version(void);

@@ -1,6 +1,7 @@
 """ctypes binding of include/adr.h.  Argument marshalling only."""
 from __future__ import annotations
 
+import contextlib
 import ctypes
 import os
 from dataclasses import dataclass
@@ -10,15 +11,27 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libadr.so")
+_DEBUG_LIB_PATH = os.path.join(_HERE, "libadr_debug.so")   # the same sources with -DADR_DEBUG_BOUNDS
 
 ADR_BF16, ADR_FP8_E4M3, ADR_F32 = 0, 1, 2
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_MFMA_GRID = 0, 1, 2, 3
 PARTIALS_ONLY = 16
 SINGLE_PARTITION_ITEMS = 32
+WORKSPACE_READY = 64
+DEBUG_EXPIRE_WAITS = 128
+
+
+def GRID_CUS(n: int) -> int:
+    """Flag bits that size the resident kernel's grid for n compute units (ADR_GRID_CUS)."""
+    if not 0 < n < 4096:
+        raise ValueError("compute units out of range")
+    return n << 16
+
 
 EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention", "adr_decode_step",
            "adr_decode_merge", "adr_lse_merge", "adr_probe_stream_read", "adr_probe_copy",
            "adr_stream_create_cu_mask", "adr_stream_destroy", "adr_stream_fault_count",
+           "adr_decode_read_status", "adr_decode_kernel_choice", "adr_kernel_name", "adr_debug_bounds_status",
            "adr_offload_bound_mem", "adr_offload_bound_comp", "adr_offload_bound", "adr_need_offload",
            "adr_graph_capacity", "adr_pack_qkv", "adr_scatter_rows",
            "adr_status_string", "adr_version")
@@ -41,23 +54,52 @@ class _CCache(ctypes.Structure):
                 ("Hkv", ctypes.c_int), ("d", ctypes.c_int), ("dtype", ctypes.c_int)]
 
 
+class _CBoundsRecord(ctypes.Structure):
+    _fields_ = [("count", ctypes.c_uint32), ("kind", ctypes.c_int32), ("row", ctypes.c_int32),
+                ("index", ctypes.c_int32), ("value", ctypes.c_int32)]
+
+
 _lib = None
+_release_lib = None
+_debug_lib = None
 
 
 def library_path() -> str:
     return _LIB_PATH
 
 
+@contextlib.contextmanager
+def debug_library():
+    """Inside the block every function of this module calls the debug build (libadr_debug.so)."""
+    global _lib, _debug_lib
+    if _debug_lib is None:
+        if not os.path.exists(_DEBUG_LIB_PATH):
+            raise ImportError("%s is missing: build it with `python -m paper_2503_20552_amd.build --debug`"
+                              % _DEBUG_LIB_PATH)
+        _debug_lib = _declare(ctypes.CDLL(_DEBUG_LIB_PATH))
+    load_library()
+    _lib = _debug_lib
+    try:
+        yield _debug_lib
+    finally:
+        _lib = _release_lib
+
+
 def load_library():
     """Load libadr.so; fails loudly when it has not been built."""
-    global _lib
+    global _lib, _release_lib
     if _lib is not None:
         return _lib
     if not os.path.exists(_LIB_PATH):
         raise ImportError(
             "%s is missing: build it with `python -m paper_2503_20552_amd.build` "
             "(there is no fallback path)" % _LIB_PATH)
-    lib = ctypes.CDLL(_LIB_PATH)
+    _lib = _release_lib = _declare(ctypes.CDLL(_LIB_PATH))
+    return _lib
+
+
+def _declare(lib):
+    """Argument and result types of every entry point."""
     vp, i32, i64, f32, sz, u32 = (ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float,
                                   ctypes.c_size_t, ctypes.c_uint)
     lib.adr_kv_append.restype = i32
@@ -104,7 +146,14 @@ def load_library():
     lib.adr_status_string.argtypes = [i32]
     lib.adr_version.restype = i32
     lib.adr_version.argtypes = []
-    _lib = lib
+    lib.adr_decode_read_status.restype = i32
+    lib.adr_decode_read_status.argtypes = [vp, sz, i32, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_uint32)]
+    lib.adr_decode_kernel_choice.restype = i32
+    lib.adr_decode_kernel_choice.argtypes = [ctypes.POINTER(_CCache), i32, i32, i32, i32, u32]
+    lib.adr_kernel_name.restype = ctypes.c_char_p
+    lib.adr_kernel_name.argtypes = [i32]
+    lib.adr_debug_bounds_status.restype = i32
+    lib.adr_debug_bounds_status.argtypes = [ctypes.POINTER(_CBoundsRecord), i32]
     return lib
 
 
@@ -195,6 +244,38 @@ def adr_stream_fault_count() -> int:
     n = ctypes.c_uint64(0)
     _check(load_library().adr_stream_fault_count(ctypes.byref(n)), "adr_stream_fault_count")
     return int(n.value)
+
+
+def adr_decode_read_status(workspace: torch.Tensor, B: int, Hq: int, d: int, max_seq_len: int,
+                           partition_tokens: int) -> int:
+    """Waits that expired in calls on this workspace since its control area was last cleared."""
+    n = ctypes.c_uint32(0)
+    _check(load_library().adr_decode_read_status(workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                                 B, Hq, d, int(max_seq_len), int(partition_tokens), ctypes.byref(n)),
+           "adr_decode_read_status")
+    return int(n.value)
+
+
+def adr_decode_kernel_choice(cache: "KVCache", B: int, Hq: int, max_seq_len: int, partition_tokens: int,
+                             flags: int = KERNEL_AUTO) -> int:
+    cs = cache.c_struct()
+    rc = load_library().adr_decode_kernel_choice(ctypes.byref(cs), B, Hq, int(max_seq_len), int(partition_tokens),
+                                                 int(flags))
+    if rc < 0:
+        raise AdrError(-rc, "adr_decode_kernel_choice")
+    return int(rc)
+
+
+def adr_kernel_name(kernel: int) -> str:
+    return load_library().adr_kernel_name(int(kernel)).decode()
+
+
+def adr_debug_bounds_status(reset: bool = False) -> dict:
+    """The debug build's record of out-of-range table entries and positions (see debug_library)."""
+    rec = _CBoundsRecord()
+    _check(load_library().adr_debug_bounds_status(ctypes.byref(rec), int(bool(reset))), "adr_debug_bounds_status")
+    return {"count": int(rec.count), "kind": int(rec.kind), "row": int(rec.row), "index": int(rec.index),
+            "value": int(rec.value)}
 
 
 def adr_status_string(status: int) -> str:

@@ -1,9 +1,11 @@
 """Build libadr.so (the gfx950 HIP library) in-tree with hipcc.
 
-    python -m paper_2503_20552_amd.build
+    python -m paper_2503_20552_amd.build [--debug]
 
 Each .hip file under csrc/ is compiled to an object in csrc/_build/ and the
-objects are linked into paper_2503_20552_amd/libadr.so.
+objects are linked into paper_2503_20552_amd/libadr.so.  --debug builds the same
+sources with -DADR_DEBUG_BOUNDS into libadr_debug.so (objects in csrc/_build/debug/):
+the build that records out-of-range page ids and append positions.
 """
 from __future__ import annotations
 
@@ -28,9 +30,12 @@ def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def _compile(name: str) -> str:
-    obj = os.path.join(OBJ, name[:-4] + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, name), "-o", obj]
+DEBUG_LIB = os.path.join(HERE, "libadr_debug.so")
+
+
+def _compile(name: str, obj_dir: str = OBJ, extra=()) -> str:
+    obj = os.path.join(obj_dir, name[:-4] + ".o")
+    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, name), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines()
                     if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
@@ -41,18 +46,21 @@ def _compile(name: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build(verbose: bool = True, debug: bool = False) -> str:
+    obj_dir = os.path.join(OBJ, "debug") if debug else OBJ
+    lib = DEBUG_LIB if debug else LIB
+    extra = ("-DADR_DEBUG_BOUNDS=1",) if debug else ()
+    os.makedirs(obj_dir, exist_ok=True)
     names = sources()
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(names))) as ex:
-        objs = list(ex.map(_compile, names))
-    tmp = LIB + ".tmp%d" % os.getpid()
+        objs = list(ex.map(lambda n: _compile(n, obj_dir, extra), names))
+    tmp = lib + ".tmp%d" % os.getpid()
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
-    os.replace(tmp, LIB)
+    os.replace(tmp, lib)
     if verbose:
-        print("built", LIB, "from", ", ".join(names))
-    return LIB
+        print("built", lib, "from", ", ".join(names))
+    return lib
 
 
 if __name__ == "__main__":
-    build()
+    build(debug="--debug" in sys.argv[1:])

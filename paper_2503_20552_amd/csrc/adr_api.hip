@@ -1,7 +1,10 @@
-// Host side of the C ABI: argument checks and kernel dispatch.  Nothing here
-// allocates, synchronises or copies; every entry point only enqueues kernels.
+// Host side of the C ABI: argument checks and kernel dispatch.  The attention, append, merge and
+// copy entry points only enqueue kernels: they never allocate, synchronise or copy.  (The status
+// readers at the end synchronise; that is what they are for.)
 #include "../../include/adr.h"
 #include "adr_device.h"
+
+#include <atomic>
 
 namespace adr {
 hipError_t launch_kv_append(const AppendParams &p, bool fp8, hipStream_t stream);
@@ -48,11 +51,83 @@ int64_t max_parts_for(int max_seq_len, int partition_tokens)
 
 size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Layout of a split pass's workspace: partial outputs, their lse values, then the control area
+// (one status block and one block per launch of the resident kernel: 512 rows each).
+struct WorkspacePlan {
+    size_t part_o_bytes = 0, part_lse_bytes = 0, control_bytes = 0;
+    size_t total() const { return part_o_bytes + part_lse_bytes + control_bytes; }
+    int control_words() const { return (int)(control_bytes / 4); }
+};
+
+WorkspacePlan plan_workspace(int B, int Hq, int d, int max_seq_len, int partition_tokens)
+{
+    WorkspacePlan w;
+    if (partition_tokens < 0 || B <= 0 || Hq <= 0 || d <= 0 || max_seq_len <= 0)
+        return w;
+    if (partition_tokens > 0) {
+        const size_t rows = (size_t)B * (size_t)max_parts_for(max_seq_len, partition_tokens) * Hq;
+        w.part_o_bytes = round256(rows * d * sizeof(float));
+        w.part_lse_bytes = round256(rows * sizeof(float));
+    }
+    w.control_bytes = (size_t)adr::kControlBlockBytes * (1 + (B + 511) / 512);
+    return w;
+}
+
+// Clears a call's control area when no append kernel of the same call does it on its way.
+__global__ void control_clear_kernel(uint32_t *words, int n)
+{
+    for (int i = threadIdx.x; i < n; i += blockDim.x)
+        words[i] = 0u;
+}
+
+// ---- per-device addresses of this file's static device data -------------------------------
+// In host code the name of a static device variable is only a handle: the address a kernel may
+// use comes from hipGetSymbolAddress, once per device (every device holds its own copy).
+#ifdef ADR_DEBUG_BOUNDS
+static __device__ adr::BoundsRecord g_bounds;
+
+struct DeviceData {
+    adr::BoundsRecord *bounds = nullptr;
+};
+DeviceData g_device_data[64];
+std::atomic<int> g_device_ready[64];
+
+int device_data(const DeviceData **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return ADR_ERR_LAUNCH;
+    if (!g_device_ready[dev].load(std::memory_order_acquire)) {
+        DeviceData dd;
+        if (hipGetSymbolAddress((void **)&dd.bounds, HIP_SYMBOL(g_bounds)) != hipSuccess || !dd.bounds)
+            return ADR_ERR_LAUNCH;
+        g_device_data[dev] = dd; // two threads racing here write the same values
+        g_device_ready[dev].store(1, std::memory_order_release);
+    }
+    *out = &g_device_data[dev];
+    return ADR_OK;
+}
+#endif
+
+// Where a debug build records out-of-range table entries and positions (nullptr in a release build).
+int bounds_record(adr::BoundsRecord **out)
+{
+    *out = nullptr;
+#ifdef ADR_DEBUG_BOUNDS
+    const DeviceData *dd = nullptr;
+    const int rc = device_data(&dd);
+    if (rc != ADR_OK)
+        return rc;
+    *out = dd->bounds;
+#endif
+    return ADR_OK;
+}
+
 } // namespace
 
 extern "C" {
 
-int adr_version(void) { return 100; }
+int adr_version(void) { return 200; }
 
 int adr_stream_create_cu_mask(void **stream, const uint32_t *cu_mask, int n_words)
 {
@@ -134,6 +209,10 @@ int adr_kv_append(const adr_kv_cache *cache, const void *k_new, const void *v_ne
     p.Hkv = cache->Hkv;
     p.d = cache->d;
     p.B = B;
+    p.clear_words = nullptr;
+    p.n_clear_words = 0;
+    if (bounds_record(&p.bounds) != ADR_OK)
+        return ADR_ERR_LAUNCH;
     const hipError_t e =
         adr::launch_kv_append(p, cache->dtype == ADR_FP8_E4M3, (hipStream_t)stream);
     return e == hipSuccess ? ADR_OK : ADR_ERR_LAUNCH;
@@ -141,10 +220,7 @@ int adr_kv_append(const adr_kv_cache *cache, const void *k_new, const void *v_ne
 
 size_t adr_decode_workspace_bytes(int B, int Hq, int d, int max_seq_len, int partition_tokens)
 {
-    if (partition_tokens <= 0 || B <= 0 || Hq <= 0 || d <= 0 || max_seq_len <= 0)
-        return 0;
-    const size_t rows = (size_t)B * (size_t)max_parts_for(max_seq_len, partition_tokens) * Hq;
-    return round256(rows * d * sizeof(float)) + round256(rows * sizeof(float));
+    return plan_workspace(B, Hq, d, max_seq_len, partition_tokens).total();
 }
 
 namespace {
@@ -153,6 +229,45 @@ struct NewToken {
     const void *k, *v;
     int64_t row_stride;
 };
+
+// Which kernel serves a pass (negative: the status to return).
+enum { KERNEL_VALU = ADR_KERNEL_VALU, KERNEL_STREAM = ADR_KERNEL_MFMA, KERNEL_GRID = ADR_KERNEL_MFMA_GRID };
+
+int choose_kernel(const adr_kv_cache *cache, int B, int Hq, int max_seq_len, int partition_tokens, unsigned flags)
+{
+    const int G = Hq / cache->Hkv;
+    const int d = cache->d;
+    const unsigned want = flags & 0xFu;
+    const bool fp8 = cache->dtype == ADR_FP8_E4M3;
+    if (want == ADR_KERNEL_VALU)
+        return adr::decode_valu_supports(d, G) ? KERNEL_VALU : -ADR_ERR_UNSUPPORTED;
+    if (want == ADR_KERNEL_MFMA_GRID)
+        return !fp8 && adr::decode_mfma_supports(d, G) ? KERNEL_GRID : -ADR_ERR_UNSUPPORTED;
+    if (want == ADR_KERNEL_MFMA) {
+        if (adr::decode_stream_supports(d, G, B))
+            return KERNEL_STREAM;
+        return !fp8 && adr::decode_mfma_supports(d, G) ? KERNEL_GRID : -ADR_ERR_UNSUPPORTED;
+    }
+    if (want != ADR_KERNEL_AUTO)
+        return -ADR_ERR_UNSUPPORTED;
+    // Measured on MI355X: the resident-workgroup kernel wins on split passes with many items
+    // (groups of up to four heads always; wider groups from 2048 (request, kv-head) pairs
+    // on: +11 % at 256 requests x 8 kv-heads, G = 8; about even at a quarter of that);
+    // whole-row items and small passes of wide groups run faster one workgroup per item.
+    const bool splits = partition_tokens > 0 && max_seq_len > partition_tokens;
+    const bool many = (int64_t)B * cache->Hkv >= 2048;
+    // An fp8 cache has the resident-workgroup kernel and the vector-ALU one only.
+    if ((fp8 || (splits && (G <= 4 || many))) && adr::decode_stream_supports(d, G, B))
+        return KERNEL_STREAM;
+    if (!fp8 && adr::decode_mfma_supports(d, G))
+        return KERNEL_GRID;
+    if (adr::decode_valu_supports(d, G))
+        return KERNEL_VALU;
+    return -ADR_ERR_UNSUPPORTED;
+}
+
+constexpr unsigned kFlagBits = 0xFu | ADR_PARTIALS_ONLY | ADR_SINGLE_PARTITION_ITEMS | ADR_WORKSPACE_READY |
+                               ADR_DEBUG_EXPIRE_WAITS | (0xFFFu << 16);
 
 int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, int64_t q_row_stride,
                      const adr_kv_cache *cache, const int32_t *block_table, int max_pages_per_req,
@@ -184,58 +299,23 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
         return ADR_ERR_UNSUPPORTED;
     if (partition_tokens < 0 || partition_tokens % cache->page_size != 0)
         return ADR_ERR_SHAPE;
-    if (flags & ~(0xFu | ADR_PARTIALS_ONLY | ADR_SINGLE_PARTITION_ITEMS))
+    if (flags & ~kFlagBits)
         return ADR_ERR_UNSUPPORTED;
     const int G = Hq / cache->Hkv;
     const int d = cache->d;
-    const unsigned want = flags & 0xFu;
     const bool fp8 = cache->dtype == ADR_FP8_E4M3;
-    enum { VALU, MFMA_GRID, MFMA_STREAM } kernel;
-    if (want == ADR_KERNEL_VALU) {
-        if (!adr::decode_valu_supports(d, G))
-            return ADR_ERR_UNSUPPORTED;
-        kernel = VALU;
-    } else if (want == ADR_KERNEL_MFMA_GRID) {
-        if (fp8 || !adr::decode_mfma_supports(d, G))
-            return ADR_ERR_UNSUPPORTED;
-        kernel = MFMA_GRID;
-    } else if (want == ADR_KERNEL_MFMA) {
-        if (adr::decode_stream_supports(d, G, B))
-            kernel = MFMA_STREAM;
-        else if (!fp8 && adr::decode_mfma_supports(d, G))
-            kernel = MFMA_GRID;
-        else
-            return ADR_ERR_UNSUPPORTED;
-    } else if (want == ADR_KERNEL_AUTO) {
-        // Measured on MI355X: the resident-workgroup kernel wins on split passes with many items
-        // (groups of up to four heads always; wider groups from 2048 (request, kv-head) pairs
-        // on: +11 % at 256 requests x 8 kv-heads, G = 8; about even at a quarter of that);
-        // whole-row items and small passes of wide groups run faster one workgroup per item.
-        const bool splits = partition_tokens > 0 && max_seq_len > partition_tokens;
-        const bool many = (int64_t)B * cache->Hkv >= 2048;
-        // An fp8 cache has the resident-workgroup kernel and the vector-ALU one only.
-        if ((fp8 || (splits && (G <= 4 || many))) && adr::decode_stream_supports(d, G, B))
-            kernel = MFMA_STREAM;
-        else if (!fp8 && adr::decode_mfma_supports(d, G))
-            kernel = MFMA_GRID;
-        else if (adr::decode_valu_supports(d, G))
-            kernel = VALU;
-        else
-            return ADR_ERR_UNSUPPORTED;
-    } else {
-        return ADR_ERR_UNSUPPORTED;
-    }
+    const int kernel = choose_kernel(cache, B, Hq, max_seq_len, partition_tokens, flags);
+    if (kernel < 0)
+        return -kernel;
     const int64_t max_parts = max_parts_for(max_seq_len, partition_tokens);
     if ((int64_t)B * cache->Hkv * max_parts > 0x7fffffffLL)
         return ADR_ERR_SHAPE;
     const bool split = partition_tokens > 0 && max_parts > 1;
-    if (split) {
-        if (!workspace)
-            return ADR_ERR_WORKSPACE;
-        if (((uintptr_t)workspace & 255u) != 0 ||
-            workspace_bytes < adr_decode_workspace_bytes(B, Hq, d, max_seq_len, partition_tokens))
-            return ADR_ERR_WORKSPACE;
-    }
+    const WorkspacePlan plan = plan_workspace(B, Hq, d, max_seq_len, partition_tokens);
+    const bool workspace_fits =
+        workspace && ((uintptr_t)workspace & 255u) == 0 && plan.total() > 0 && workspace_bytes >= plan.total();
+    if (split && !workspace_fits)
+        return ADR_ERR_WORKSPACE;
     if (B == 0)
         return ADR_OK;
 
@@ -253,10 +333,12 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
     p.part_o = nullptr;
     p.part_lse = nullptr;
     if (split) {
-        const size_t rows = (size_t)B * (size_t)max_parts * Hq;
         p.part_o = (float *)workspace;
-        p.part_lse = (float *)((char *)workspace + round256(rows * d * sizeof(float)));
+        p.part_lse = (float *)((char *)workspace + plan.part_o_bytes);
     }
+    // A workspace that is large enough also carries the call's control area (an unsplit pass
+    // may come with one too); a call without one falls back on the library's static pool.
+    p.control = workspace_fits ? (uint32_t *)((char *)workspace + plan.part_o_bytes + plan.part_lse_bytes) : nullptr;
     p.max_pages = max_pages_per_req;
     p.page_shift = cache->page_size == 16 ? 0 : cache->page_size == 32 ? 1 : 2;
     p.B = B;
@@ -270,6 +352,15 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
     p.out_f32 = out_dtype == ADR_F32;
     p.scale_log2e = scale * adr::kLog2e;
     p.coalesce = !(flags & ADR_SINGLE_PARTITION_ITEMS);
+    p.spin_limit = (flags & ADR_DEBUG_EXPIRE_WAITS) ? 0 : adr::kSpinLimit;
+    p.grid_cus = (int)((flags >> 16) & 0xFFFu);
+    if (bounds_record(&p.bounds) != ADR_OK)
+        return ADR_ERR_LAUNCH;
+
+    // The control area must be all zero when the resident kernel starts and when a merge reads the
+    // status block.  Kernels that never touch it leave the merge without a status to read.
+    const bool uses_control = p.control && (kernel == KERNEL_STREAM || (flags & ADR_PARTIALS_ONLY));
+    const bool clear_control = uses_control && !(flags & ADR_WORKSPACE_READY);
 
     // The new token goes in first: the append kernel, with the token index taken from seq_lens.
     if (nt) {
@@ -291,12 +382,19 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
         ap.Hkv = cache->Hkv;
         ap.d = d;
         ap.B = B;
+        ap.clear_words = clear_control ? p.control : nullptr; // on its way, for the kernels behind it
+        ap.n_clear_words = clear_control ? plan.control_words() : 0;
+        ap.bounds = p.bounds;
         if (adr::launch_kv_append(ap, fp8, (hipStream_t)stream) != hipSuccess)
             return ADR_ERR_LAUNCH;
+    } else if (clear_control) {
+        control_clear_kernel<<<1, 64, 0, (hipStream_t)stream>>>(p.control, plan.control_words());
+        if (hipGetLastError() != hipSuccess)
+            return ADR_ERR_LAUNCH;
     }
-    hipError_t e = kernel == MFMA_STREAM ? adr::launch_decode_stream(p, d, fp8, (hipStream_t)stream)
-                   : kernel == MFMA_GRID ? adr::launch_decode_mfma(p, d, (hipStream_t)stream)
-                                         : adr::launch_decode_valu(p, d, fp8, (hipStream_t)stream);
+    hipError_t e = kernel == KERNEL_STREAM ? adr::launch_decode_stream(p, d, fp8, (hipStream_t)stream)
+                   : kernel == KERNEL_GRID ? adr::launch_decode_mfma(p, d, (hipStream_t)stream)
+                                           : adr::launch_decode_valu(p, d, fp8, (hipStream_t)stream);
     if (e != hipSuccess)
         return ADR_ERR_LAUNCH;
     if (split && !(flags & ADR_PARTIALS_ONLY)) {
@@ -314,6 +412,7 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
         mp.heads = Hq;
         mp.d = d;
         mp.out_f32 = p.out_f32;
+        mp.status = uses_control ? p.control : nullptr;
         e = adr::launch_lse_merge(mp, (hipStream_t)stream);
         if (e != hipSuccess)
             return ADR_ERR_LAUNCH;
@@ -364,15 +463,15 @@ int adr_decode_merge(void *out, adr_dtype out_dtype, float *lse, const int32_t *
     const int64_t max_parts = max_parts_for(max_seq_len, partition_tokens);
     if (partition_tokens == 0 || max_parts <= 1 || B == 0)
         return ADR_OK;
-    if (!workspace || ((uintptr_t)workspace & 255u) != 0 ||
-        workspace_bytes < adr_decode_workspace_bytes(B, Hq, d, max_seq_len, partition_tokens))
+    const WorkspacePlan plan = plan_workspace(B, Hq, d, max_seq_len, partition_tokens);
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < plan.total())
         return ADR_ERR_WORKSPACE;
-    const size_t rows = (size_t)B * (size_t)max_parts * Hq;
     adr::MergeParams mp;
     mp.out = out;
     mp.lse_out = lse;
     mp.part_o = (const float *)workspace;
-    mp.part_lse = (const float *)((const char *)workspace + round256(rows * d * sizeof(float)));
+    mp.part_lse = (const float *)((const char *)workspace + plan.part_o_bytes);
+    mp.status = (const uint32_t *)((const char *)workspace + plan.part_o_bytes + plan.part_lse_bytes);
     mp.part_offsets = nullptr;
     mp.seq_lens = seq_lens;
     mp.partition_tokens = partition_tokens;
@@ -413,7 +512,71 @@ int adr_lse_merge(void *out, adr_dtype out_dtype, float *lse_out, const float *p
     mp.heads = heads;
     mp.d = d;
     mp.out_f32 = out_dtype == ADR_F32;
+    mp.status = nullptr;
     return adr::launch_lse_merge(mp, (hipStream_t)stream) == hipSuccess ? ADR_OK : ADR_ERR_LAUNCH;
+}
+
+int adr_decode_kernel_choice(const adr_kv_cache *cache, int B, int Hq, int max_seq_len, int partition_tokens,
+                             unsigned flags)
+{
+    const int rc = check_cache(cache);
+    if (rc != ADR_OK)
+        return -rc;
+    if (B < 0 || Hq <= 0 || Hq % cache->Hkv != 0 || max_seq_len < 0 || partition_tokens < 0)
+        return -ADR_ERR_SHAPE;
+    return choose_kernel(cache, B, Hq, max_seq_len, partition_tokens, flags);
+}
+
+const char *adr_kernel_name(int kernel)
+{
+    switch (kernel) {
+    case ADR_KERNEL_VALU: return "decode_valu_kernel";
+    case ADR_KERNEL_MFMA: return "decode_stream_kernel";
+    case ADR_KERNEL_MFMA_GRID: return "decode_mfma_kernel";
+    default: return "";
+    }
+}
+
+int adr_decode_read_status(const void *workspace, size_t workspace_bytes, int B, int Hq, int d, int max_seq_len,
+                           int partition_tokens, uint32_t *expired_waits)
+{
+    if (!workspace || !expired_waits)
+        return ADR_ERR_NULL;
+    const WorkspacePlan plan = plan_workspace(B, Hq, d, max_seq_len, partition_tokens);
+    if (plan.total() == 0 || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < plan.total())
+        return ADR_ERR_WORKSPACE;
+    const char *status = (const char *)workspace + plan.part_o_bytes + plan.part_lse_bytes;
+    uint32_t word = 0;
+    if (hipMemcpy(&word, status + 4 * adr::kStatusExpiredWaits, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess)
+        return ADR_ERR_LAUNCH;
+    *expired_waits = word;
+    return ADR_OK;
+}
+
+int adr_debug_bounds_status(adr_bounds_record *record, int reset)
+{
+#ifdef ADR_DEBUG_BOUNDS
+    if (!record)
+        return ADR_ERR_NULL;
+    adr::BoundsRecord *dev = nullptr;
+    if (bounds_record(&dev) != ADR_OK || !dev)
+        return ADR_ERR_LAUNCH;
+    adr::BoundsRecord host;
+    if (hipMemcpy(&host, dev, sizeof(host), hipMemcpyDeviceToHost) != hipSuccess)
+        return ADR_ERR_LAUNCH;
+    record->count = host.count;
+    record->kind = host.kind;
+    record->row = host.row;
+    record->index = host.index;
+    record->value = host.value;
+    if (reset && hipMemset(dev, 0, sizeof(host)) != hipSuccess)
+        return ADR_ERR_LAUNCH;
+    return ADR_OK;
+#else
+    (void)record;
+    (void)reset;
+    return ADR_ERR_UNSUPPORTED;
+#endif
 }
 
 int adr_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream)

@@ -14,12 +14,38 @@ constexpr int kThreads = kWaves * 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f; // "no score seen yet": finite so that differences never give NaN
+constexpr int kSpinLimit = 1 << 24; // polls of a flag in on-chip memory before a wait on another wave is declared
+                                    // failed (seconds: an unsplit row of millions of tokens keeps a wave busy for
+                                    // tens of ms)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// Control area of a call, in the caller's workspace behind the partial results (or, for a call
+// without a workspace, in a small static pool): one block of call status, then one block per
+// launch of the resident-workgroup kernel (a batch goes out as one launch per 512 rows).
+// Every word is zero when no launch is using the area: an initialising kernel (or the append
+// kernel of adr_decode_step) clears it, and each launch hands its own block back cleared.
+constexpr int kControlBlockBytes = 256;
+constexpr int kControlBlockWords = kControlBlockBytes / 4;
+enum {
+    kStatusExpiredWaits = 0, // call status, word 0: bounded waits that expired since the area was cleared
+    kLaunchTicket = 0,       // launch block: next ticket
+    kLaunchFinished = 1,     //   workgroups that are through
+    kLaunchExpired = 2,      //   bounded waits that expired in this launch
+};
+
+// What a debug build (-DADR_DEBUG_BOUNDS) records about table entries and positions that fall
+// outside the pool or the table: how many, and the first one.
+struct BoundsRecord {
+    uint32_t count;
+    int32_t kind; // 0 none, 1 attention: page id outside the pool, 2 append: position outside the table,
+                  // 3 append: page id outside the pool
+    int32_t row, index, value;
+};
 
 // Everything adr_decode_attention's kernels need, passed by value.
 struct DecodeParams {
@@ -42,6 +68,10 @@ struct DecodeParams {
     int out_f32;          // 1: out is fp32, 0: bf16
     int coalesce;         // the resident kernel may take runs of partitions as one item
     float scale_log2e;    // softmax scale * log2(e): scores are kept in base 2
+    uint32_t *control;    // control area of the call (status block first), or nullptr: the static pool
+    int spin_limit;       // polls before a wait on another wave is declared failed
+    int grid_cus;         // > 0: size the resident kernel's grid for this many compute units
+    BoundsRecord *bounds; // debug builds: where out-of-range entries are recorded (else nullptr)
 };
 
 struct MergeParams {
@@ -53,6 +83,8 @@ struct MergeParams {
     int partition_tokens;        //   [b*max_parts, b*max_parts + ceil(min(seq_len,max_seq_len)/partition_tokens))
     int max_parts, max_seq_len;  //   and rows with <= 1 partition are left alone
     int B, heads, d, out_f32;
+    const uint32_t *status;      // call status block of the pass that wrote the partials, or nullptr: when
+                                 // its expired-waits word is not zero every row gets NaN
 };
 
 struct AppendParams {
@@ -66,13 +98,36 @@ struct AppendParams {
     const int32_t *seq_lens;
     int max_seq_len;
     int max_pages, num_pages, page_size, Hkv, d, B;
+    uint32_t *clear_words; // control area the first workgroup clears on its way (adr_decode_step), or nullptr
+    int n_clear_words;
+    BoundsRecord *bounds;  // debug builds only
 };
 
+// positions == nullptr: the row's last token as the attention kernels will see it.  A row
+// longer than the host's bound is attended up to the bound and appends nothing: writing at the
+// bound would overwrite an older token.
 __device__ __forceinline__ int append_position(const AppendParams &p, int b)
 {
     if (p.positions)
         return p.positions[b];
-    return min(max(p.seq_lens[b], 0), p.max_seq_len) - 1;
+    const int L = p.seq_lens[b];
+    return L > p.max_seq_len ? -1 : L - 1;
+}
+
+__device__ __forceinline__ void record_out_of_bounds(BoundsRecord *rec, int kind, int row, int index, int value)
+{
+#ifdef ADR_DEBUG_BOUNDS
+    if (rec) {
+        atomicAdd(&rec->count, 1u);
+        if (atomicCAS(&rec->kind, 0, kind) == 0) {
+            rec->row = row;
+            rec->index = index;
+            rec->value = value;
+        }
+    }
+#else
+    (void)rec; (void)kind; (void)row; (void)index; (void)value;
+#endif
 }
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -152,6 +207,20 @@ __device__ __forceinline__ int clamp_page(int page, int num_pages)
 __device__ __forceinline__ int pool_tile(int table_entry, int tile, int num_pages, int page_shift)
 {
     return (clamp_page(table_entry, num_pages) << page_shift) | (tile & ((1 << page_shift) - 1));
+}
+
+// The same, for kernels that know which row they are in: a debug build records an entry that
+// had to be clamped (the release build clamps silently).
+__device__ __forceinline__ int pool_tile_checked(int table_entry, int tile, int num_pages, int page_shift,
+                                                 BoundsRecord *rec, int row)
+{
+#ifdef ADR_DEBUG_BOUNDS
+    if ((unsigned)table_entry >= (unsigned)num_pages && (threadIdx.x & 63) == 0)
+        record_out_of_bounds(rec, 1, row, tile >> page_shift, table_entry);
+#else
+    (void)rec; (void)row;
+#endif
+    return pool_tile(table_entry, tile, num_pages, page_shift);
 }
 
 // Number of partitions of a row of L tokens (>= 1, so that an empty row still

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
         u32x4 ka[4];
         const int last = pg + (pg_end - 1 - pg) / kWaves * kWaves; // this wave's last page
         const int sh = p.page_shift; // a cache page is 1 << sh tiles of 16 tokens
-#define ADR_TILE(T) pool_tile(bt[(T) >> sh], (T), p.num_pages, sh)
+#define ADR_TILE(T) pool_tile_checked(bt[(T) >> sh], (T), p.num_pages, sh, p.bounds, b)
         int page = ADR_TILE(pg);
         int page_next = ADR_TILE(min(pg + kWaves, last));
         load_page(A, tile0, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes), k_lane,

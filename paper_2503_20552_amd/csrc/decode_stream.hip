@@ -48,12 +48,18 @@
 // folded into the score scale and the V scale into the weights.
 //
 // Every wait on another wave is bounded: a wave that has polled an LDS word for
-// far longer than any legitimate delay raises a fault counter (readable through
-// adr_stream_fault_count) and carries on, so the grid always drains.
+// far longer than any legitimate delay counts a fault -- in the launch's control
+// block, in the call's status word and in a device-wide counter (readable through
+// adr_stream_fault_count) -- and carries on, so the grid always drains.  From then
+// on its workgroup stores NaN instead of results, and the last workgroup of the
+// launch to finish overwrites the launch's rows of out / lse (and the partitions'
+// lse) with NaN: a row that a broken hand-shake left stale or wrong cannot pass as
+// a result.  (A split pass's merge reads the status word and does the same.)
 //
-// The ticket counter and a finished-workgroups counter live in a small pool of
-// static device words that are zero whenever no launch is using them: the last
-// workgroup to finish puts both back to zero.
+// The ticket counter and a finished-workgroups counter live in the launch's control
+// block: in the caller's workspace when there is one, else in a small pool of static
+// device words.  They are zero whenever no launch is using them: the last workgroup
+// to finish puts them back to zero.
 #include "mfma_page.h"
 
 #include <algorithm>
@@ -64,8 +70,8 @@ namespace adr {
 constexpr int kMaxStreamB = 512;
 constexpr int kTicketSlots = 256; // counter pairs: the lower half serves direct launches, the upper half recorded ones
 constexpr int kQueue = 8;          // item records kept in LDS (power of two)
-constexpr int kSpinLimit = 1 << 24; // polls of an LDS word before a wait is declared failed (seconds: an
-                                    // unsplit row of millions of tokens keeps a wave busy for tens of ms)
+// polls of an LDS word before a wait is declared failed: DecodeParams::spin_limit, kSpinLimit by default
+// (seconds: an unsplit row of millions of tokens keeps a wave busy for tens of ms)
 constexpr int kSpinLimitAfterFault = 64; // ... once a wait of this workgroup has failed
 constexpr int kCoalesceItems = 8192;     // items (of the caller's partition size) per doubling of the item size:
                                          // measured neutral below about 16K items, -5 to -10 % at 40K
@@ -82,12 +88,15 @@ template <bool FP8> struct Geo {
     static constexpr int kMaxStages = FP8 ? 6 : 4;
 };
 
-__device__ uint32_t g_tickets[kTicketSlots][2];
+// Launch control blocks for calls without a workspace, and the status word such calls share.
+__device__ uint32_t g_pool[kTicketSlots][4];
+__device__ uint32_t g_pool_status[kControlBlockWords];
 __device__ unsigned long long g_stream_faults;
 
 struct StreamParams {
     DecodeParams d;
-    uint32_t *ticket; // {next ticket, workgroups finished}
+    uint32_t *ctl;    // the launch's control block: kLaunchTicket, kLaunchFinished, kLaunchExpired
+    uint32_t *status; // the call's status block
     unsigned long long *faults;
     int pt;           // tokens per partition (2^30 when the pass is not split)
     int stages;       // ring stages per wave (2 .. Geo::kMaxStages)
@@ -221,25 +230,78 @@ __device__ __forceinline__ void flag_add_async(int *word, int value)
     asm volatile("ds_add_u32 %0, %1" ::"v"(lds_address(word)), "v"(value) : "memory");
 }
 
+// What a wave needs to wait for another one: the workgroup's "a wait has expired" flag in LDS,
+// and for how long to poll.
+struct Waits {
+    int *failed;
+    int limit;
+};
+
+// The kernel's argument block.  Code that runs only when something has gone wrong reads what it
+// needs of the parameters from here, so that none of it occupies registers through the item loop.
+__device__ __forceinline__ const __attribute__((address_space(4))) StreamParams *argument_block()
+{
+    return (const __attribute__((address_space(4))) StreamParams *)__builtin_amdgcn_kernarg_segment_ptr();
+}
+
+// An expired wait is counted in the launch's control block, in the call's status word and
+// device-wide, and flagged in the workgroup.
+__device__ __forceinline__ void count_fault(const Waits &w)
+{
+    if ((threadIdx.x & 63) == 0) {
+        flag_write(w.failed, 1);
+        atomicAdd(argument_block()->faults, 1ull);
+        atomicAdd(argument_block()->ctl + kLaunchExpired, 1u);
+        atomicAdd(argument_block()->status + kStatusExpiredWaits, 1u);
+    }
+}
+
 // Poll an LDS word until it holds `want`.  Returns false (and counts a fault)
 // when it never does; the caller then goes on without what it waited for.
-__device__ __forceinline__ bool poll_equal(int *word, int want, int *failed, unsigned long long *faults)
+__device__ __forceinline__ bool poll_equal(int *word, int want, const Waits &w)
 {
-    int limit = kSpinLimit;
+    int limit = w.limit;
     for (int spin = 0; spin < limit; ++spin) {
         if (__builtin_amdgcn_readfirstlane(flag_read(word)) == want) {
             lds_order();
             return true;
         }
-        if (spin == 0 && __builtin_amdgcn_readfirstlane(flag_read(failed)))
-            limit = kSpinLimitAfterFault;
+        if (spin == 0 && __builtin_amdgcn_readfirstlane(flag_read(w.failed)))
+            limit = min(limit, kSpinLimitAfterFault);
         __builtin_amdgcn_s_sleep(1);
     }
-    if ((threadIdx.x & 63) == 0) {
-        flag_write(failed, 1);
-        atomicAdd(faults, 1ull);
-    }
+    count_fault(w);
     return false;
+}
+
+// The same, reading a second word (`also`) in the round trips of the first; *also_value
+// receives what it held at the last poll (or holds now, when no poll was made).
+__device__ __forceinline__ bool poll_equal_also(int *word, int want, const Waits &w, const int *also,
+                                                int *also_value)
+{
+    int limit = w.limit, extra = 0;
+    bool ok = false;
+    for (int spin = 0; spin < limit && !ok; ++spin) {
+        int v;
+        asm volatile("ds_read_b32 %0, %2\n\tds_read_b32 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(v), "=&v"(extra)
+                     : "v"(lds_address(word)), "v"(lds_address(also))
+                     : "memory");
+        ok = __builtin_amdgcn_readfirstlane(v) == want;
+        if (!ok) {
+            if (spin == 0 && __builtin_amdgcn_readfirstlane(flag_read(w.failed)))
+                limit = min(limit, kSpinLimitAfterFault);
+            __builtin_amdgcn_s_sleep(1);
+        }
+    }
+    if (ok) {
+        lds_order();
+    } else {
+        count_fault(w);
+        extra = flag_read(also);
+    }
+    *also_value = __builtin_amdgcn_readfirstlane(extra);
+    return ok;
 }
 
 __device__ __forceinline__ void publish(Rec &rec, const Item &it, int seq)
@@ -258,8 +320,8 @@ __device__ __forceinline__ void publish(Rec &rec, const Item &it, int seq)
 
 // `also`, when given, is another LDS word read in the same round trip (every dependent LDS access
 // costs a wave a few hundred cycles here); its value comes back in *also_value.
-__device__ __forceinline__ Item fetch(Rec &rec, int seq, int *failed, unsigned long long *faults,
-                                      const int *also = nullptr, int *also_value = nullptr)
+__device__ __forceinline__ Item fetch(Rec &rec, int seq, const Waits &w, const int *also = nullptr,
+                                      int *also_value = nullptr)
 {
     // The record is 32 bytes; its stamp is written last, so a copy whose stamp is the
     // wanted one is whole.  The common case is one round trip.
@@ -282,7 +344,7 @@ __device__ __forceinline__ Item fetch(Rec &rec, int seq, int *failed, unsigned l
     }
     bool ok = __builtin_amdgcn_readfirstlane(lo[0]) == seq;
     if (!ok) {
-        ok = poll_equal(&rec.seq, seq, failed, faults);
+        ok = poll_equal(&rec.seq, seq, w);
         asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\ts_waitcnt lgkmcnt(0)"
                      : "=&v"(lo), "=&v"(hi)
                      : "v"(lds_address(&rec))
@@ -527,7 +589,7 @@ void decode_stream_kernel(const StreamParams sp)
     if (tid == 0)
         asm volatile("s_nop 4\n\tglobal_atomic_add %0, %1, %2, %3 sc0"
                      : "=&v"(first_ticket)
-                     : "v"(0), "v"(3), "s"(sp.ticket)
+                     : "v"(0), "v"(3), "s"(sp.ctl)
                      : "memory");
 
     // ---- partitions per row: exclusive prefix sums over the rows, four rows per thread
@@ -679,8 +741,9 @@ void decode_stream_kernel(const StreamParams sp)
     // instantiations with a fixed ring depth serve 16-token pages only).
     const int tsh = STAGES > 0 ? 0 : p.page_shift;
 
-    Item C = fetch(sh.rec[0], 0, &sh.failed, sp.faults);
-    Item N = fetch(sh.rec[1], 1, &sh.failed, sp.faults);
+    const Waits waits = {&sh.failed, p.spin_limit};
+    Item C = fetch(sh.rec[0], 0, waits);
+    Item N = fetch(sh.rec[1], 1, waits);
     issue_query(myq, sp, C, q_lane);
 
     // ---- load cursor: the next page of this wave's stream to be issued.  It runs
@@ -694,6 +757,11 @@ void decode_stream_kernel(const StreamParams sp)
     int ld_kvh = C.kvh;
     table_ptr ld_bt = (table_ptr)(p.block_table + (int64_t)C.b * p.max_pages);
     int ld_ok = 0, ld_id = 0;
+#ifdef ADR_DEBUG_BOUNDS /* the row the cursor is in, for the record of an out-of-pool page id */
+#define ADR_CURSOR_ROW (int)((ld_bt - (table_ptr)p.block_table) / p.max_pages)
+#else
+#define ADR_CURSOR_ROW 0
+#endif
 #define ADR_SETTLE()                                                                              \
     do { /* move the cursor to the next existing page and fetch its page id */                    \
         if (!ld_in_next && ld_pg >= ld_end) {                                                     \
@@ -706,7 +774,8 @@ void decode_stream_kernel(const StreamParams sp)
         }                                                                                         \
         ld_ok = ld_pg < ld_end;                                                                   \
         if (ld_ok)                                                                                \
-            ld_id = pool_tile(ld_bt[ld_pg >> tsh], ld_pg, p.num_pages, tsh);                      \
+            ld_id = pool_tile_checked(ld_bt[ld_pg >> tsh], ld_pg, p.num_pages, tsh, p.bounds,     \
+                                      ADR_CURSOR_ROW);                                            \
     } while (0)
     // Ring state: `occ` slots starting at `head` are occupied, in issue order; the
     // next load group goes to `tail`.  real_mask marks the slots that hold a page.
@@ -779,7 +848,7 @@ void decode_stream_kernel(const StreamParams sp)
         if (drawer && lane == 0)
             asm volatile("s_nop 4\n\tglobal_atomic_add %0, %1, %2, %3 sc0"
                          : "=&v"(next_ticket)
-                         : "v"(0), "v"(1), "s"(sp.ticket)
+                         : "v"(0), "v"(1), "s"(sp.ctl)
                          : "memory");
         age = 0;
 
@@ -807,8 +876,7 @@ void decode_stream_kernel(const StreamParams sp)
                 ADR_ISSUE();
             }
             if (!((real_mask >> head) & 1)) { // cannot happen; never consume a slot that holds no page
-                if (lane == 0)
-                    atomicAdd(sp.faults, 1ull);
+                count_fault(waits);
                 pg += kWaves;
                 continue;
             }
@@ -872,9 +940,9 @@ void decode_stream_kernel(const StreamParams sp)
         const int use = sp.nb == 2 ? (k >> 1) : k;
         int gen_seen = 0;
         const Item after_next =
-            fetch(sh.rec[(k + 2) & (kQueue - 1)], k + 2, &sh.failed, sp.faults, &sh.gen[buf], &gen_seen);
+            fetch(sh.rec[(k + 2) & (kQueue - 1)], k + 2, waits, &sh.gen[buf], &gen_seen);
         if (gen_seen != use)
-            poll_equal(&sh.gen[buf], use, &sh.failed, sp.faults); // the buffer's previous item has been combined
+            poll_equal(&sh.gen[buf], use, waits); // the buffer's previous item has been combined
 
         // ---- deliver this wave's share (an item past the end still takes its turn of the buffers)
         if (C.valid) {
@@ -909,7 +977,12 @@ void decode_stream_kernel(const StreamParams sp)
             const Item &Q = late ? P : C;
             const int qbuf = late ? ((k - 1) & 1) : 0;
             const int quse = late ? ((k - 1) >> 1) : k;
-            if (poll_equal(&sh.arrive[qbuf], kWaves, &sh.failed, sp.faults)) {
+            // Once a wait of this workgroup has expired (this one or an earlier one, of any wave), what
+            // the staging buffers hold cannot be trusted: the item gets NaN instead.
+            int failed_seen = 0;
+            const bool arrived = poll_equal_also(&sh.arrive[qbuf], kWaves, waits, &sh.failed, &failed_seen);
+            const bool bad = !arrived || failed_seen != 0;
+            {
                 if (Q.valid) {
                     // Two output quads per lane and round; all LDS reads of a round are issued
                     // before anything is computed, so the round costs one LDS latency, not ten.
@@ -950,8 +1023,11 @@ void decode_stream_kernel(const StreamParams sp)
                                 den += f * ml[t][w][1];
                             }
                             const float inv = den > 0.f ? 1.f / den : 0.f;
-                            const f32x4 o = acc * inv;
-                            const float lse = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
+                            const float lse_ok = den > 0.f ? (M + fast_log2(den)) * kLn2 : -INFINITY;
+                            const float lse = bad ? __builtin_nanf("") : lse_ok;
+                            f32x4 o = acc * inv;
+                            if (bad)
+                                o = f32x4{lse, lse, lse, lse};
                             const int h = Q.kvh * G + g[t];
                             if (Q.n_parts == 1) {
                                 const int64_t off = ((int64_t)Q.b * p.Hq + h) * D + c4[t];
@@ -982,7 +1058,7 @@ void decode_stream_kernel(const StreamParams sp)
                                 -INFINITY;
                     }
                 }
-                if (lane == 0) { // hand the buffer back
+                if (arrived && lane == 0) { // hand the buffer back
                     flag_write(&sh.arrive[qbuf], 0);
                     flag_write(&sh.gen[qbuf], quse + 1);
                 }
@@ -1004,25 +1080,52 @@ void decode_stream_kernel(const StreamParams sp)
 #undef ADR_ISSUE_V
 #undef ADR_ISSUE_K
 #undef ADR_SETTLE
+#undef ADR_CURSOR_ROW
 #undef ADR_FIRST_PAGE
 #undef ADR_END_PAGE
 
-    // ---- hand the counters back to zero once every workgroup is through
+    // ---- hand the launch's control block back cleared once every workgroup is through.  (Every wave's
+    // own fault counts have completed by now: they were waited for above the barrier.)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
-        const uint32_t done = atomicAdd(sp.ticket + 1, 1u);
+        int poison = 0;
+        const uint32_t done = atomicAdd(sp.ctl + kLaunchFinished, 1u);
         if (done == gridDim.x - 1) {
-            atomicExch(sp.ticket, 0u);
-            atomicExch(sp.ticket + 1, 0u);
+            poison = atomicExch(sp.ctl + kLaunchExpired, 0u) != 0u;
+            atomicExch(sp.ctl + kLaunchTicket, 0u);
+            atomicExch(sp.ctl + kLaunchFinished, 0u);
         }
+        sh.first[0] = poison;
+    }
+    __syncthreads();
+    // A wait expired somewhere in this launch: no row of it may pass as a result.  (What this needs
+    // of the parameters is read afresh from the kernel's argument block, so that none of it has to
+    // stay in registers through the loop above.)
+    if (sh.first[0]) {
+        const DecodeParams &a = argument_block()->d;
+        const int out_f32 = a.out_f32;
+        const u32x4 nan4 = out_f32 ? u32x4{0x7fc00000u, 0x7fc00000u, 0x7fc00000u, 0x7fc00000u}
+                                   : u32x4{0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u};
+        const int64_t rows = (int64_t)a.B * a.Hq;
+        const int64_t out_quads = rows * D * (out_f32 ? 4 : 2) / 16;
+        u32x4 *out4 = (u32x4 *)a.out;
+        for (int64_t i = threadIdx.x; i < out_quads; i += kThreads)
+            out4[i] = nan4;
+        float *lse = a.lse, *part_lse = a.part_lse;
+        if (lse)
+            for (int64_t i = threadIdx.x; i < rows; i += kThreads)
+                lse[i] = __builtin_nanf("");
+        if (part_lse)
+            for (int64_t i = threadIdx.x; i < rows * a.max_parts; i += kThreads)
+                part_lse[i] = __builtin_nanf("");
     }
 }
 
 namespace {
-// A launch takes the next counter pair of its half of the pool, round robin.  A recorded launch
-// keeps its pair for every replay, which is why it must not share the pool with direct launches
-// that may run beside a replay on another stream.
+// A launch without a caller's control area takes the next block of its half of the static pool,
+// round robin.  A recorded launch keeps its block for every replay, which is why it must not
+// share the pool with direct launches that may run beside a replay on another stream.
 std::atomic<unsigned> g_next_slot{0}, g_next_recorded_slot{0};
 }
 
@@ -1034,7 +1137,8 @@ bool decode_stream_supports(int d, int G, int B)
 
 namespace {
 struct DeviceInfo {
-    uint32_t *tickets = nullptr;
+    uint32_t *pool = nullptr;        // g_pool
+    uint32_t *pool_status = nullptr; // g_pool_status
     unsigned long long *faults = nullptr;
     int workgroups = 0;
 };
@@ -1052,7 +1156,9 @@ hipError_t device_info(int *dev_out)
     if (g_ready[dev].load(std::memory_order_acquire))
         return hipSuccess;
     DeviceInfo di;
-    if ((e = hipGetSymbolAddress((void **)&di.tickets, HIP_SYMBOL(g_tickets))) != hipSuccess)
+    if ((e = hipGetSymbolAddress((void **)&di.pool, HIP_SYMBOL(g_pool))) != hipSuccess)
+        return e;
+    if ((e = hipGetSymbolAddress((void **)&di.pool_status, HIP_SYMBOL(g_pool_status))) != hipSuccess)
         return e;
     if ((e = hipGetSymbolAddress((void **)&di.faults, HIP_SYMBOL(g_stream_faults))) != hipSuccess)
         return e;
@@ -1073,7 +1179,7 @@ hipError_t device_info(int *dev_out)
 } // namespace
 
 namespace {
-hipError_t launch_rows(const DecodeParams &p, int d, bool fp8, hipStream_t stream);
+hipError_t launch_rows(const DecodeParams &p, int d, bool fp8, int chunk, hipStream_t stream);
 }
 
 // The kernel's length scan holds kMaxStreamB rows; a larger batch goes out as several launches
@@ -1094,7 +1200,7 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
         c.lse = p.lse ? p.lse + (int64_t)b0 * p.Hq : nullptr;
         c.part_o = p.part_o ? p.part_o + (int64_t)b0 * p.max_parts * p.Hq * D : nullptr;
         c.part_lse = p.part_lse ? p.part_lse + (int64_t)b0 * p.max_parts * p.Hq : nullptr;
-        const hipError_t e = launch_rows(c, d, fp8, stream);
+        const hipError_t e = launch_rows(c, d, fp8, b0 / kMaxStreamB, stream);
         if (e != hipSuccess)
             return e;
     }
@@ -1102,7 +1208,7 @@ hipError_t launch_decode_stream(const DecodeParams &p, int d, bool fp8, hipStrea
 }
 
 namespace {
-hipError_t launch_rows(const DecodeParams &p, int d, bool fp8, hipStream_t stream)
+hipError_t launch_rows(const DecodeParams &p, int d, bool fp8, int chunk, hipStream_t stream)
 {
     int dev = 0;
     hipError_t e = device_info(&dev);
@@ -1145,10 +1251,16 @@ hipError_t launch_rows(const DecodeParams &p, int d, bool fp8, hipStream_t strea
     hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(stream, &capturing) != hipSuccess)
         (void)hipGetLastError();
-    const unsigned slot = capturing == hipStreamCaptureStatusNone
-                              ? g_next_slot.fetch_add(1) % (kTicketSlots / 2)
-                              : kTicketSlots / 2 + g_next_recorded_slot.fetch_add(1) % (kTicketSlots / 2);
-    sp.ticket = g_info[dev].tickets + 2 * slot;
+    if (p.control) { // the caller's control area: status block, then one block per launch of the call
+        sp.status = p.control;
+        sp.ctl = p.control + (size_t)(1 + chunk) * kControlBlockWords;
+    } else {
+        const unsigned slot = capturing == hipStreamCaptureStatusNone
+                                  ? g_next_slot.fetch_add(1) % (kTicketSlots / 2)
+                                  : kTicketSlots / 2 + g_next_recorded_slot.fetch_add(1) % (kTicketSlots / 2);
+        sp.status = g_info[dev].pool_status;
+        sp.ctl = g_info[dev].pool + 4 * slot;
+    }
     sp.faults = g_info[dev].faults;
     sp.pt = p.partition_tokens > 0 ? p.partition_tokens : (1 << 30);
     sp.stages = stages;
@@ -1157,7 +1269,9 @@ hipError_t launch_rows(const DecodeParams &p, int d, bool fp8, hipStream_t strea
     // A stream may be confined to some of the compute units: size the grid for those.
     // (Not asked of a stream that is recording a graph: queries can end a capture.)
     int cus = g_info[dev].workgroups;
-    if (capturing == hipStreamCaptureStatusNone) {
+    if (p.grid_cus > 0) {
+        cus = std::min(cus, p.grid_cus);
+    } else if (capturing == hipStreamCaptureStatusNone) {
         uint32_t mask[32] = {0};
         if (hipExtStreamGetCUMask(stream, 32, mask) == hipSuccess) {
             int bits = 0;

@@ -104,7 +104,7 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(const DecodeParam
     const int pg_end = (t1 + kPageSize - 1) / kPageSize;
 
     for (int pg = t0 / kPageSize + wave; pg < pg_end; pg += kWaves) {
-        const int page = pool_tile(bt[pg >> p.page_shift], pg, p.num_pages, p.page_shift); // a 16-token tile
+        const int page = pool_tile_checked(bt[pg >> p.page_shift], pg, p.num_pages, p.page_shift, p.bounds, b); // a 16-token tile
         const int64_t base = ((int64_t)page * kPageSize * Hkv + kvh) * D + c * 8;
         Row8<FP8> kr[U], vr[U];
 #pragma unroll

@@ -3,6 +3,36 @@
 
 namespace adr {
 
+// adr_decode_step: the append kernel runs right before the attention kernels of the same call,
+// so its first workgroup also clears the call's control area for them.
+__device__ __forceinline__ void clear_control(const AppendParams &p)
+{
+    if (p.clear_words && blockIdx.x == 0)
+        for (int i = threadIdx.x; i < p.n_clear_words; i += blockDim.x)
+            p.clear_words[i] = 0u;
+}
+
+// The page a row's token goes to, or -1 when the row is skipped (a padded row, a position past
+// the row's table, a page id outside the pool; a debug build records the latter two, once per
+// row: `report` is true in one thread of the row's workgroups).
+__device__ __forceinline__ int append_page(const AppendParams &p, int b, int pos, bool report)
+{
+    if (pos < 0)
+        return -1;
+    if (pos / p.page_size >= p.max_pages) {
+        if (report)
+            record_out_of_bounds(p.bounds, 2, b, pos, p.max_pages * p.page_size);
+        return -1;
+    }
+    const int page = p.block_table[(int64_t)b * p.max_pages + pos / p.page_size];
+    if (page < 0 || page >= p.num_pages) {
+        if (report)
+            record_out_of_bounds(p.bounds, 3, b, pos / p.page_size, page);
+        return -1;
+    }
+    return page;
+}
+
 // bf16 cache: one workgroup per request copies the Hkv*d bf16 of K and of V in
 // 16-byte pieces.  The destination row of a token is contiguous.  The first pieces are
 // read before the position and the page are looked up (they depend on neither), so the
@@ -15,11 +45,10 @@ __global__ __launch_bounds__(128) void kv_append_bf16_kernel(const AppendParams 
     const int first = min((int)threadIdx.x * 8, row - 8);
     const u32x4 k0 = *(const u32x4 *)(p.k_new + src + first);
     const u32x4 v0 = *(const u32x4 *)(p.v_new + src + first);
+    clear_control(p);
     const int pos = append_position(p, b);
-    if (pos < 0 || pos / p.page_size >= p.max_pages)
-        return;
-    const int page = p.block_table[(int64_t)b * p.max_pages + pos / p.page_size];
-    if (page < 0 || page >= p.num_pages)
+    const int page = append_page(p, b, pos, threadIdx.x == 0);
+    if (page < 0)
         return;
     const int64_t dst = ((int64_t)page * p.page_size + pos % p.page_size) * row;
     if ((int)threadIdx.x * 8 < row) {
@@ -64,11 +93,10 @@ template <int D>
 __global__ __launch_bounds__(64) void kv_append_fp8_kernel(const AppendParams p)
 {
     const int b = blockIdx.x / p.Hkv, h = blockIdx.x % p.Hkv;
+    clear_control(p);
     const int pos = append_position(p, b);
-    if (pos < 0 || pos / p.page_size >= p.max_pages)
-        return;
-    const int page = p.block_table[(int64_t)b * p.max_pages + pos / p.page_size];
-    if (page < 0 || page >= p.num_pages)
+    const int page = append_page(p, b, pos, threadIdx.x == 0 && h == 0);
+    if (page < 0)
         return;
     const int slot = pos % p.page_size;
     constexpr int E = D / 64;

@@ -4,7 +4,8 @@
 // consecutive output elements (16-byte loads of the fp32 partials).  One sweep
 // over the row's partitions, sixteen at a time with all their loads issued before
 // any is used, carrying a running maximum of the lse values (fixed order, so the
-// result is the same from run to run).
+// result is the same from run to run).  When the attention pass left a non-zero
+// expired-waits word in the call's status block, every row gets NaN instead.
 #include "adr_device.h"
 
 namespace adr {
@@ -19,6 +20,21 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(const MergeParams p)
     if (row >= (int64_t)p.B * p.heads)
         return;
     const int b = (int)(row / p.heads), h = (int)(row % p.heads);
+
+    // The pass that wrote the partials reported a broken hand-shake between its waves: no row of
+    // the call may pass as a result (rows with one partition included).
+    if (p.status && p.status[kStatusExpiredWaits] != 0u) {
+        const float nan = __builtin_nanf("");
+        const int64_t off = row * D + col;
+        if (p.out_f32) {
+            *(f32x4 *)((float *)p.out + off) = f32x4{nan, nan, nan, nan};
+        } else {
+            *(u32x2 *)((uint16_t *)p.out + off) = u32x2{0x7fc07fc0u, 0x7fc07fc0u};
+        }
+        if (p.lse_out && col == 0)
+            p.lse_out[row] = nan;
+        return;
+    }
 
     int first, count;
     if (p.part_offsets) {

@@ -65,7 +65,7 @@ NULL, SHAPE, UNSUP, WORK = 1, 2, 3, 4
     (dict(partition_tokens=-16), SHAPE),
     (dict(B=-1), SHAPE),
     (dict(out_dtype=adr.ADR_FP8_E4M3), UNSUP),
-    (dict(flags=4), UNSUP), (dict(flags=64), UNSUP),
+    (dict(flags=4), UNSUP), (dict(flags=256), UNSUP), (dict(flags=1 << 28), UNSUP),
     (dict(Hq=2 * 32, q_row_stride=64 * 128), UNSUP),   # G = 32
     (dict(partition_tokens=16), WORK),         # split needs a workspace
     (dict(partition_tokens=16, workspace=FAKE, workspace_bytes=16), WORK),
@@ -150,11 +150,53 @@ def test_merge_rejects_bad_arguments():
 
 
 def test_workspace_size_formula():
-    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1000, 0) == 0
+    control = 256 * 2                            # a status block and one launch block (up to 512 rows)
+    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1000, 0) == control      # an unsplit pass: control area only
     rows = 4 * 2 * 8                             # ceil(1000/512) = 2 partitions
-    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1000, 512) == rows * 128 * 4 + 256
-    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1024, 512) == rows * 128 * 4 + 256
-    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1025, 512) > rows * 128 * 4 + 256
+    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1000, 512) == rows * 128 * 4 + 256 + control
+    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1024, 512) == rows * 128 * 4 + 256 + control
+    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1025, 512) > rows * 128 * 4 + 256 + control
+    assert adr.adr_decode_workspace_bytes(513, 8, 128, 1000, 0) == 256 * 3    # two launches of the resident kernel
+    assert adr.adr_decode_workspace_bytes(0, 8, 128, 1000, 512) == 0
+    assert adr.adr_decode_workspace_bytes(4, 8, 128, 1000, -16) == 0
+
+
+def test_new_flags_are_accepted_and_status_readers_check_their_arguments():
+    lib = adr.load_library()
+    ok_flags = adr.WORKSPACE_READY | adr.DEBUG_EXPIRE_WAITS | adr.GRID_CUS(64) | adr.SINGLE_PARTITION_ITEMS
+    assert attention(cache(), B=0, flags=ok_flags) == 0
+    n = ctypes.c_uint32(7)
+    assert lib.adr_decode_read_status(None, 1 << 20, 2, 8, 128, 64, 16, ctypes.byref(n)) == NULL
+    assert lib.adr_decode_read_status(FAKE, 1 << 20, 2, 8, 128, 64, 16, None) == NULL
+    assert lib.adr_decode_read_status(FAKE, 16, 2, 8, 128, 64, 16, ctypes.byref(n)) == WORK      # too small
+    assert lib.adr_decode_read_status(FAKE + 16, 1 << 20, 2, 8, 128, 64, 16, ctypes.byref(n)) == WORK  # misaligned
+    assert lib.adr_decode_read_status(FAKE, 1 << 20, 0, 8, 128, 64, 16, ctypes.byref(n)) == WORK # no such workspace
+    assert n.value == 7
+    rec = binding._CBoundsRecord()
+    assert lib.adr_debug_bounds_status(ctypes.byref(rec), 0) == UNSUP       # the release build records nothing
+
+
+def test_kernel_choice_is_reported_by_the_library():
+    lib = adr.load_library()
+    def choice(c, **kw):
+        a = dict(B=256, Hq=32, max_seq_len=8192, part=512, flags=0)
+        a.update(kw)
+        return lib.adr_decode_kernel_choice(ctypes.byref(c), a["B"], a["Hq"], a["max_seq_len"], a["part"], a["flags"])
+    gqa = cache(Hkv=8)
+    assert choice(gqa) == adr.KERNEL_MFMA                         # split pass, groups of four: resident kernel
+    assert choice(gqa, part=0) == adr.KERNEL_MFMA_GRID            # whole rows: one workgroup per item
+    assert choice(gqa, B=128, Hq=64) == adr.KERNEL_MFMA_GRID      # a small pass of wide groups
+    assert choice(gqa, Hq=64) == adr.KERNEL_MFMA                  # 2048 (request, kv-head) pairs
+    assert choice(cache(Hkv=8, d=64)) == adr.KERNEL_VALU
+    fp8 = cache(Hkv=8, dtype=adr.ADR_FP8_E4M3, k_scale=FAKE, v_scale=FAKE)
+    assert choice(fp8) == adr.KERNEL_MFMA and choice(fp8, part=0) == adr.KERNEL_MFMA
+    assert choice(gqa, flags=adr.KERNEL_VALU) == adr.KERNEL_VALU
+    assert choice(gqa, Hq=128, flags=adr.KERNEL_VALU) == -UNSUP   # groups of sixteen
+    assert choice(gqa, Hq=7) == -SHAPE and choice(cache(d=96)) == -UNSUP
+    assert lib.adr_kernel_name(adr.KERNEL_MFMA) == b"decode_stream_kernel"
+    assert lib.adr_kernel_name(adr.KERNEL_MFMA_GRID) == b"decode_mfma_kernel"
+    assert lib.adr_kernel_name(adr.KERNEL_VALU) == b"decode_valu_kernel"
+    assert lib.adr_kernel_name(0) == b""
 
 
 def test_cu_mask_stream_and_fault_count_reject_bad_arguments():

@@ -57,7 +57,7 @@ def run_two_calls(wl, b, flags, partition_tokens, out_dtype=torch.float32, max_s
     table, seq = dev(b.block_table), dev(b.seq_lens)
     if max_seq_len is None:
         max_seq_len = int(b.seq_lens.max())
-    pos = dev((np.minimum(np.maximum(b.seq_lens, 0), max_seq_len) - 1).astype(np.int32))
+    pos = dev(np.where(b.seq_lens > max_seq_len, -1, b.seq_lens - 1).astype(np.int32))
     out = torch.full((wl.B, wl.Hq, wl.d), float("nan"), dtype=out_dtype, device="cuda:0")
     lse = torch.full((wl.B, wl.Hq), float("nan"), dtype=torch.float32, device="cuda:0")
     nbytes = adr.adr_decode_workspace_bytes(wl.B, wl.Hq, wl.d, max_seq_len, partition_tokens)
@@ -72,7 +72,9 @@ def run_two_calls(wl, b, flags, partition_tokens, out_dtype=torch.float32, max_s
 def oracle_step(wl, b, max_seq_len=None):
     kh, vh = W.bits(b.k_cache).copy(), W.bits(b.v_cache).copy()
     lens = b.seq_lens if max_seq_len is None else np.minimum(b.seq_lens, max_seq_len)
-    oracle.kv_append(kh, vh, W.bits(b.k_new), W.bits(b.v_new), b.block_table, (lens - 1).astype(np.int32))
+    # a row longer than the host's bound is attended up to the bound and appends nothing
+    pos = b.seq_lens - 1 if max_seq_len is None else np.where(b.seq_lens > max_seq_len, -1, b.seq_lens - 1)
+    oracle.kv_append(kh, vh, W.bits(b.k_new), W.bits(b.v_new), b.block_table, pos.astype(np.int32))
     ref, ref_lse, _ = oracle.decode_attention(W.bits(b.q), kh, vh, b.block_table, lens.astype(np.int32), wl.scale)
     return ref, ref_lse, kh, vh
 
@@ -162,13 +164,17 @@ def test_step_skips_rows_whose_last_page_has_no_valid_entry():
         assert np.array_equal(W.bits(kc), kh) and np.array_equal(W.bits(vc), vh)
 
 
-def test_step_truncated_by_max_seq_len_appends_at_the_truncated_end():
-    wl, b = make_case(17, 8, 2, 128, [300, 50, 129])
+def test_step_row_longer_than_max_seq_len_is_truncated_and_appends_nothing():
+    """Rows 0 and 2 exceed the bound: they attend their first 128 tokens and the cache keeps the older
+    token that sits at the bound; row 3 is exactly at the bound and appends as usual."""
+    wl, b = make_case(17, 8, 2, 128, [300, 50, 129, 128])
     say("step max_seq_len")
     for kernel in ("mfma", "valu"):
         out, lse, kc, vc = run_step(wl, b, KERNELS[kernel], 64, max_seq_len=128)
         ref, ref_lse, kh, vh = oracle_step(wl, b, max_seq_len=128)
         assert np.array_equal(W.bits(kc), kh) and np.array_equal(W.bits(vc), vh)
+        before = W.bits(b.k_cache)
+        assert np.array_equal(kh[b.block_table[0, 7]], before[b.block_table[0, 7]]), "row 0 must not append"
         compare(out, lse, ref, ref_lse, what="step truncated %s" % kernel)
 
 

@@ -8,7 +8,12 @@ the kernel would poll a flag or finish a step; a seeded random scheduler interle
 all workgroups, letting single waves run far ahead.  Checked: every page of every (request,
 kv-head) is consumed exactly once, by the slot that holds its page id; no live ring slot is
 overwritten; null slots are passed over within the guard; a staging buffer is never written before
-its previous item was combined; every item is combined exactly once; every wave terminates."""
+its previous item was combined; every item is combined exactly once; every wave terminates.
+
+A second mode models the kernel with every wait expiring at once (the state a broken hand-shake, or
+the library's test flag, puts it in): the results are then worthless by design, and what is checked
+is that every wave still terminates, that every page it touches lies inside its row's table, and that
+every item it would store lies inside the batch -- i.e. that the failure mode is safe to run."""
 import random
 
 import numpy as np
@@ -16,7 +21,7 @@ import pytest
 
 KW = 4; KQ = 8
 
-def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshift=0):
+def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshift=0, waits_expire=False):
     rnd = random.Random(seed)
     B = len(seq_lens)
     pt_given = pt_arg if pt_arg > 0 else (1 << 30)
@@ -50,7 +55,7 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshi
         return it
     consumed = {}      # (b, kvh, page_index) -> count
     combined = {}      # (b, kvh, part) -> count
-    stats = dict(pairs=0, singles=0, nulls=0, polls=0)
+    stats = dict(pairs=0, singles=0, nulls=0, polls=0, expired=0, stored=0)
 
     def wave_proc(wg, wave):
         sh = wg["sh"]
@@ -59,6 +64,10 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshi
         def fetch(idx):
             while sh["rec"][idx % KQ]["seq"] != idx:
                 stats["polls"] += 1
+                if waits_expire:     # the record never came: the wave goes on as if the item were past the end
+                    stats["expired"] += 1
+                    yield
+                    return dict(valid=False, b=0, kvh=0, part=0, t1=0, n_parts=1)
                 yield
             return dict(sh["rec"][idx % KQ]["it"])
         C = yield from fetch(0)
@@ -69,7 +78,7 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshi
                 cur.update(in_next=1, pg=first_page(N), end=end_page(N), b=N["b"], kvh=N["kvh"])
             cur["ok"] = cur["pg"] < cur["end"]
             if cur["ok"]:
-                assert 0 <= cur["pg"] < block_table.shape[1]
+                assert 0 <= cur["pg"] < block_table.shape[1] and 0 <= cur["b"] < B
                 cur["id"] = int(block_table[cur["b"], cur["pg"]])
         ring = [None] * S
         st = dict(head=0, tail=0, occ=0)
@@ -106,8 +115,9 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshi
                 pair = pg + KW < pg_end and ring[second] not in (None, "null")
                 for slot, want in ((st["head"], pg),) + (((second, pg + KW),) if pair else ()):
                     b_, kvh_, pg_, id_ = ring[slot]
-                    assert (b_, kvh_, pg_) == (C["b"], C["kvh"], want), ("wrong slot", ring[slot], C, want)
-                    assert id_ == int(block_table[C["b"], want])
+                    if not waits_expire:
+                        assert (b_, kvh_, pg_) == (C["b"], C["kvh"], want), ("wrong slot", ring[slot], C, want)
+                        assert id_ == int(block_table[C["b"], want])
                     consumed[(b_, kvh_, pg_)] = consumed.get((b_, kvh_, pg_), 0) + 1
                     ring[slot] = None
                 if pair:
@@ -124,9 +134,12 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshi
             use = (k // 2) if NB == 2 else k
             while sh["gen"][buf] != use:
                 stats["polls"] += 1
+                if waits_expire:
+                    stats["expired"] += 1
+                    break
                 yield
             if C["valid"]:
-                assert sh["stage_owner"][buf][wave] is None, "staging overwritten"
+                assert waits_expire or sh["stage_owner"][buf][wave] is None, "staging overwritten"
                 sh["stage_owner"][buf][wave] = k
             sh["arrive"][buf] += 1
             # The combining goes round the waves.  With two staging buffers it is one item late: at
@@ -137,14 +150,25 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshi
                 q = k - late
                 qbuf = (q % 2) if NB == 2 else 0
                 Q = P if late else C
+                arrived = True
                 while sh["arrive"][qbuf] != KW:
                     stats["polls"] += 1
+                    if waits_expire:
+                        stats["expired"] += 1
+                        arrived = False
+                        break
                     yield
                 if Q["valid"]:
-                    assert all(o == q for o in sh["stage_owner"][qbuf]), ("combine mix", sh["stage_owner"][qbuf], q)
+                    # what the combining wave stores (results, or NaN after an expired wait) goes to the item's place
+                    assert 0 <= Q["b"] < B and 0 <= Q["kvh"] < Hkv
+                    assert 0 <= (Q["part"] << cshift) < max(1, -(-max_seq_len // pt_given)) or pt_arg == 0
+                    stats["stored"] += 1
+                    if not waits_expire:
+                        assert all(o == q for o in sh["stage_owner"][qbuf]), ("combine mix", sh["stage_owner"][qbuf], q)
                     key = (Q["b"], Q["kvh"], Q["part"]); combined[key] = combined.get(key, 0) + 1
                     sh["stage_owner"][qbuf] = [None] * KW
-                sh["arrive"][qbuf] = 0; sh["gen"][qbuf] = ((q // 2) if NB == 2 else q) + 1
+                if arrived:
+                    sh["arrive"][qbuf] = 0; sh["gen"][qbuf] = ((q // 2) if NB == 2 else q) + 1
             P = C
             yield
             C = N
@@ -177,6 +201,8 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshi
                 live.pop(i); break
         steps += 1
         assert steps < 50_000_000, "no progress: deadlock"
+    if waits_expire:
+        return stats    # no coverage is promised; termination and the range checks above are the point
     # coverage
     exp_pages = {}
     for b in range(B):
@@ -219,3 +245,12 @@ def test_protocol_covers_every_page_once_and_terminates(trial, lens, Hkv, pt, S,
     table = rng.integers(0, 10000, size=(len(lens), maxp)).astype(np.int32)
     stats = run(lens, table, Hkv, pt, int(lens.max()), n_wg, S, NB, trial, cshift)
     assert stats["pairs"] + stats["singles"] > 0 or int(lens.max()) == 0
+
+
+@pytest.mark.parametrize("trial,lens,Hkv,pt,S,NB,n_wg,cshift", CASES, ids=[str(c[0]) for c in CASES])
+def test_with_every_wait_expiring_the_waves_still_terminate_inside_their_rows(trial, lens, Hkv, pt, S, NB, n_wg, cshift):
+    rng = np.random.default_rng(300 + trial)
+    maxp = max(1, (int(lens.max()) + 15) // 16)
+    table = rng.integers(0, 10000, size=(len(lens), maxp)).astype(np.int32)
+    stats = run(lens, table, Hkv, pt, int(lens.max()), n_wg, S, NB, trial, cshift, waits_expire=True)
+    assert stats["expired"] > 0
