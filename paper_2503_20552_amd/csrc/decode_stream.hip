@@ -1103,21 +1103,22 @@ void decode_stream_kernel(const StreamParams sp)
     // of the parameters is read afresh from the kernel's argument block, so that none of it has to
     // stay in registers through the loop above.)
     if (sh.first[0]) {
-        const DecodeParams &a = argument_block()->d;
-        const int out_f32 = a.out_f32;
+        const auto *ab = argument_block();
+        const int out_f32 = ab->d.out_f32;
         const u32x4 nan4 = out_f32 ? u32x4{0x7fc00000u, 0x7fc00000u, 0x7fc00000u, 0x7fc00000u}
                                    : u32x4{0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u};
-        const int64_t rows = (int64_t)a.B * a.Hq;
+        const int64_t rows = (int64_t)ab->d.B * ab->d.Hq;
         const int64_t out_quads = rows * D * (out_f32 ? 4 : 2) / 16;
-        u32x4 *out4 = (u32x4 *)a.out;
+        u32x4 *out4 = (u32x4 *)ab->d.out;
         for (int64_t i = threadIdx.x; i < out_quads; i += kThreads)
             out4[i] = nan4;
-        float *lse = a.lse, *part_lse = a.part_lse;
+        float *lse = ab->d.lse, *part_lse = ab->d.part_lse;
+        const int max_parts = ab->d.max_parts;
         if (lse)
             for (int64_t i = threadIdx.x; i < rows; i += kThreads)
                 lse[i] = __builtin_nanf("");
         if (part_lse)
-            for (int64_t i = threadIdx.x; i < rows * a.max_parts; i += kThreads)
+            for (int64_t i = threadIdx.x; i < rows * max_parts; i += kThreads)
                 part_lse[i] = __builtin_nanf("");
     }
 }
