@@ -173,6 +173,27 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
                          unsigned flags, void *stream);
 
 /*
+ * adr_decode_attention_static -- adr_decode_attention for callers that cannot allocate device
+ * memory and have no workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments, checks and results as adr_decode_attention
+ * (the same kernels run); the workspace (partitions' results and the control area) is a static
+ * device array inside the library, ADR_STATIC_SCRATCH_BYTES long, which every device the library
+ * runs on holds until the process ends.  The call itself allocates and frees nothing.
+ *   - ADR_ERR_WORKSPACE when adr_decode_workspace_bytes(B, Hq, d, max_seq_len, partition_tokens)
+ *     exceeds ADR_STATIC_SCRATCH_BYTES (B = 256, Hq = 32, d = 128, 8192-token rows in partitions
+ *     of 512 need 68.6 MiB).  ADR_WORKSPACE_READY is refused (ADR_ERR_UNSUPPORTED).
+ *   - Every call on a device uses that device's one array: calls that overlap on one device
+ *     (two streams, or a replay beside a direct call) race on it.  The array keeps the last
+ *     call's contents; each call clears what it needs cleared (the control area) with a small
+ *     kernel of its own.
+ */
+#define ADR_STATIC_SCRATCH_BYTES (96u << 20)
+int adr_decode_attention_static(void *out, adr_dtype out_dtype, float *lse, const void *q, int64_t q_row_stride,
+                                const adr_kv_cache *cache, const int32_t *block_table, int max_pages_per_req,
+                                const int32_t *seq_lens, int B, int Hq, float scale, int max_seq_len,
+                                int partition_tokens, unsigned flags, void *stream);
+
+/*
  * adr_decode_step -- one decode step of the executor (Sec. 2.1 steps (1)-(2), Sec. 3.2.1): the
  * new token's K/V join the cache and the row attends over all its tokens, the new one included.
  * Same result, in `out`, `lse` and the cache, as

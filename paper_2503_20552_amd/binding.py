@@ -28,7 +28,8 @@ def GRID_CUS(n: int) -> int:
     return n << 16
 
 
-EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention", "adr_decode_step",
+EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention", "adr_decode_attention_static",
+           "adr_decode_step",
            "adr_decode_merge", "adr_lse_merge", "adr_probe_stream_read", "adr_probe_copy",
            "adr_stream_create_cu_mask", "adr_stream_destroy", "adr_stream_fault_count",
            "adr_decode_read_status", "adr_decode_kernel_choice", "adr_kernel_name", "adr_debug_bounds_status",
@@ -109,6 +110,9 @@ def _declare(lib):
     lib.adr_decode_attention.restype = i32
     lib.adr_decode_attention.argtypes = [vp, i32, vp, vp, i64, ctypes.POINTER(_CCache), vp, i32,
                                          vp, i32, i32, f32, i32, i32, vp, sz, u32, vp]
+    lib.adr_decode_attention_static.restype = i32
+    lib.adr_decode_attention_static.argtypes = [vp, i32, vp, vp, i64, ctypes.POINTER(_CCache), vp, i32,
+                                                vp, i32, i32, f32, i32, i32, u32, vp]
     lib.adr_decode_step.restype = i32
     lib.adr_decode_step.argtypes = [vp, i32, vp, vp, i64, vp, vp, i64, ctypes.POINTER(_CCache), vp, i32,
                                     vp, i32, i32, f32, i32, i32, vp, sz, u32, vp]
@@ -405,6 +409,25 @@ def adr_decode_attention(out: torch.Tensor, q: torch.Tensor, cache: KVCache,
         ws_ptr, ws_bytes, int(flags), _stream_handle(stream)), "adr_decode_attention")
 
 
+STATIC_SCRATCH_BYTES = 96 << 20
+
+
+def adr_decode_attention_static(out: torch.Tensor, q: torch.Tensor, cache: KVCache,
+                                block_table: torch.Tensor, seq_lens: torch.Tensor, scale: float,
+                                max_seq_len: int, partition_tokens: int = 0,
+                                lse: Optional[torch.Tensor] = None, flags: int = KERNEL_AUTO,
+                                stream=None) -> None:
+    """adr_decode_attention with the library's static device array as the workspace (no allocation)."""
+    lib = load_library()
+    cs = cache.c_struct()
+    odt, lse_ptr, qp, qstride, B, Hq, _, _ = _attention_args(out, q, cache, block_table, seq_lens, None, lse)
+    _check(lib.adr_decode_attention_static(
+        out.data_ptr(), odt, lse_ptr, qp, qstride,
+        ctypes.byref(cs), _i32(block_table, "block_table"), block_table.shape[1],
+        _i32(seq_lens, "seq_lens"), B, Hq, float(scale), int(max_seq_len), int(partition_tokens),
+        int(flags), _stream_handle(stream)), "adr_decode_attention_static")
+
+
 def adr_decode_step(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
                     cache: KVCache, block_table: torch.Tensor, seq_lens: torch.Tensor, scale: float,
                     max_seq_len: int, partition_tokens: int = 0,
@@ -483,3 +506,4 @@ def adr_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
         raise ValueError("dst smaller than src")
     _check(load_library().adr_probe_copy(dst.data_ptr(), src.data_ptr(), n - n % 16,
                                          _stream_handle(stream)), "adr_probe_copy")
+

@@ -81,12 +81,18 @@ __global__ void control_clear_kernel(uint32_t *words, int n)
 }
 
 // ---- per-device addresses of this file's static device data -------------------------------
-// In host code the name of a static device variable is only a handle: the address a kernel may
-// use comes from hipGetSymbolAddress, once per device (every device holds its own copy).
+// adr_decode_attention_static keeps its workspace in `scratch`, a static device array, because
+// its callers cannot allocate.  In host code the name of a static device variable is only a
+// handle: the address a kernel (or a copy) may use comes from hipGetSymbolAddress, once per
+// device with that device current (every device holds its own copy of the array at its own
+// address).  Everything below uses those addresses, never the names.
+static __device__ __align__(256) unsigned char scratch[ADR_STATIC_SCRATCH_BYTES];
 #ifdef ADR_DEBUG_BOUNDS
 static __device__ adr::BoundsRecord g_bounds;
+#endif
 
 struct DeviceData {
+    unsigned char *scratch = nullptr;
     adr::BoundsRecord *bounds = nullptr;
 };
 DeviceData g_device_data[64];
@@ -99,15 +105,18 @@ int device_data(const DeviceData **out)
         return ADR_ERR_LAUNCH;
     if (!g_device_ready[dev].load(std::memory_order_acquire)) {
         DeviceData dd;
+        if (hipGetSymbolAddress((void **)&dd.scratch, HIP_SYMBOL(scratch)) != hipSuccess || !dd.scratch)
+            return ADR_ERR_LAUNCH;
+#ifdef ADR_DEBUG_BOUNDS
         if (hipGetSymbolAddress((void **)&dd.bounds, HIP_SYMBOL(g_bounds)) != hipSuccess || !dd.bounds)
             return ADR_ERR_LAUNCH;
+#endif
         g_device_data[dev] = dd; // two threads racing here write the same values
         g_device_ready[dev].store(1, std::memory_order_release);
     }
     *out = &g_device_data[dev];
     return ADR_OK;
 }
-#endif
 
 // Where a debug build records out-of-range table entries and positions (nullptr in a release build).
 int bounds_record(adr::BoundsRecord **out)
@@ -273,7 +282,7 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
                      const adr_kv_cache *cache, const int32_t *block_table, int max_pages_per_req,
                      const int32_t *seq_lens, int B, int Hq, float scale, int max_seq_len,
                      int partition_tokens, void *workspace, size_t workspace_bytes, unsigned flags,
-                     void *stream, const NewToken *nt)
+                     void *stream, const NewToken *nt, bool static_scratch = false)
 {
     const int rc = check_cache(cache);
     if (rc != ADR_OK)
@@ -312,6 +321,20 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
         return ADR_ERR_SHAPE;
     const bool split = partition_tokens > 0 && max_parts > 1;
     const WorkspacePlan plan = plan_workspace(B, Hq, d, max_seq_len, partition_tokens);
+    if (static_scratch) { // the library's own array stands in for the caller's workspace
+        if (plan.total() > (size_t)ADR_STATIC_SCRATCH_BYTES)
+            return ADR_ERR_WORKSPACE;
+        if (flags & ADR_WORKSPACE_READY)
+            return ADR_ERR_UNSUPPORTED; // calls of other sizes keep their control areas elsewhere in the array
+        if (B == 0)
+            return ADR_OK;
+        const DeviceData *dd = nullptr;
+        const int drc = device_data(&dd);
+        if (drc != ADR_OK)
+            return drc;
+        workspace = dd->scratch;
+        workspace_bytes = ADR_STATIC_SCRATCH_BYTES;
+    }
     const bool workspace_fits =
         workspace && ((uintptr_t)workspace & 255u) == 0 && plan.total() > 0 && workspace_bytes >= plan.total();
     if (split && !workspace_fits)
@@ -432,6 +455,16 @@ int adr_decode_attention(void *out, adr_dtype out_dtype, float *lse, const void 
     return decode_attention(out, out_dtype, lse, q, q_row_stride, cache, block_table, max_pages_per_req,
                             seq_lens, B, Hq, scale, max_seq_len, partition_tokens, workspace,
                             workspace_bytes, flags, stream, nullptr);
+}
+
+int adr_decode_attention_static(void *out, adr_dtype out_dtype, float *lse, const void *q, int64_t q_row_stride,
+                                const adr_kv_cache *cache, const int32_t *block_table, int max_pages_per_req,
+                                const int32_t *seq_lens, int B, int Hq, float scale, int max_seq_len,
+                                int partition_tokens, unsigned flags, void *stream)
+{
+    return decode_attention(out, out_dtype, lse, q, q_row_stride, cache, block_table, max_pages_per_req,
+                            seq_lens, B, Hq, scale, max_seq_len, partition_tokens, nullptr, 0, flags, stream,
+                            nullptr, true);
 }
 
 int adr_decode_step(void *out, adr_dtype out_dtype, float *lse, const void *q, int64_t q_row_stride,
