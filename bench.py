@@ -119,6 +119,14 @@ def main():
                     help="capture one step (all layers: append, attention, merge) into a HIP graph and replay "
                          "it; prints its own JSON line with eager and replayed times and the CPU time spent "
                          "enqueueing a step either way")
+    ap.add_argument("--graph-table", action="store_true",
+                    help="record the step for batch capacities on an interval grid (adr_graph_table_*) and replay "
+                         "the smallest fit for several batch sizes; prints its own JSON line: per capacity the GPU "
+                         "time of a step and the CPU time to enqueue it, eager and replayed, and what a table "
+                         "recorded for a masked stream costs with and without ADR_GRID_CUS")
+    ap.add_argument("--attention-cus", type=int, default=0,
+                    help="with --corun-gemm: the attention on a stream masked to the first N compute units, the "
+                         "matrix products on the others (0 = two plain streams)")
     ap.add_argument("--cu-sweep", action="store_true",
                     help="with --corun-gemm: repeat the measurement with the attention confined to 32, 64, ... "
                          "compute units and the matrix products to the others")
@@ -186,17 +194,19 @@ def main():
                 e2.record()
                 events.append((e0, e1, e2))
 
-    if args.corun_gemm:
-        return corun_gemm(args, wl, st, one_step, bytes_per_token, layers, part)
-    if args.graph:
-        return graph_replay(args, wl, st, one_step, out, bytes_per_token, layers, part)
-
     if args.probe_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
         adr.adr_probe_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.corun_gemm:
+        return corun_gemm(args, wl, st, one_step, bytes_per_token, layers, part)
+    if args.graph:
+        return graph_replay(args, wl, st, one_step, out, bytes_per_token, layers, part)
+    if args.graph_table:
+        return graph_table(args, wl, st, out, ws, bytes_per_token, layers, part, flags)
 
     for s in range(Wm):
         one_step(s)
@@ -389,82 +399,61 @@ def corun_gemm(args, wl, st, one_step, bytes_per_token, layers, part):
     """Attention and a compute-bound neighbour sharing the GPU (the paper's colocation of the
     attention executor with prefill, Sec. 3.3): stream A runs the K timed steps, stream B runs
     bf16 8192 x 8192 x 8192 products back to back.  Each is timed alone and then together; the
-    contended figures count only work that overlapped the other stream's activity."""
+    contended figures count only work that overlapped the other stream's activity.
+    --attention-cus N confines the attention to N compute units and the products to the rest."""
     K, Wm = args.steps, args.warmup
     b = st["batch"]
-    dev = "cuda:0"
     if args.cu_sweep:
         return cu_sweep(args, wl, st, one_step, bytes_per_token, layers, part)
-    n = 8192
-    ga = W.randn_bf16((n, n), wl.seed + 50, dev)
-    gb = W.randn_bf16((n, n), wl.seed + 51, dev)
-    gc = torch.empty((n, n), dtype=torch.bfloat16, device=dev)
-    flop = 2.0 * n ** 3
-    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()      # default priority, both
+    total_cus = torch.cuda.get_device_properties(0).multi_processor_count
+    nb = Neighbour(wl)
     tokens = [int(b.lens_before.sum()) + wl.B * (s + 1) for s in range(Wm, Wm + K)]
     kv_bytes = layers * sum(tokens) * bytes_per_token
+    handles = []
+    if args.attention_cus:
+        n_attn = args.attention_cus
+        handles = [adr.adr_stream_create_cu_mask([i < n_attn for i in range(total_cus)]),
+                   adr.adr_stream_create_cu_mask([i >= n_attn for i in range(total_cus)])]
+        sa, sb = (torch.cuda.ExternalStream(h) for h in handles)
+    else:
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()      # default priority, both
 
     def attention_pass():
         for s in range(Wm, Wm + K):
             one_step(s)
 
-    def ev():
-        return torch.cuda.Event(enable_timing=True)
-
     for _ in range(3):
-        torch.matmul(ga, gb, out=gc)
+        nb.product()
     with torch.cuda.stream(sa):
         for s in range(Wm):
             one_step(s)
     torch.cuda.synchronize()
-
-    # alone
-    a0, a1 = ev(), ev()
+    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     with torch.cuda.stream(sa):
         a0.record(); attention_pass(); a1.record()
     torch.cuda.synchronize()
     attn_alone_ms = a0.elapsed_time(a1)
-    g0, g1 = ev(), ev()
-    n_alone = 20
-    with torch.cuda.stream(sb):
-        g0.record()
-        for _ in range(n_alone):
-            torch.matmul(ga, gb, out=gc)
-        g1.record()
+    gemm_alone_ms = nb.alone_ms(sb, reps=20 if not handles else 6)
+    attn_co_ms, gemm_co_ms, n_inside = side_by_side(attention_pass, sa, nb, sb, attn_alone_ms, gemm_alone_ms)
     torch.cuda.synchronize()
-    gemm_alone_ms = g0.elapsed_time(g1) / n_alone
-
-    # together: enough products to cover the attention pass even if it slows down threefold
-    n_gemm = max(4, int(math.ceil(3.0 * attn_alone_ms / gemm_alone_ms)) + 2)
-    marks = [ev() for _ in range(n_gemm + 1)]
-    c0, c1 = ev(), ev()
-    with torch.cuda.stream(sb):
-        marks[0].record()
-        for i in range(n_gemm):
-            torch.matmul(ga, gb, out=gc)
-            marks[i + 1].record()
-    with torch.cuda.stream(sa):
-        c0.record(); attention_pass(); c1.record()
-    torch.cuda.synchronize()
-    attn_co_ms = c0.elapsed_time(c1)
-    # products that started after the attention began and ended before it finished
-    inside = [marks[i].elapsed_time(marks[i + 1]) for i in range(n_gemm)
-              if c0.elapsed_time(marks[i]) >= 0 and marks[i + 1].elapsed_time(c1) >= 0]
-    gemm_co_ms = float(np.mean(inside)) if inside else float("nan")
+    for h in handles:
+        adr.adr_stream_destroy(h)
     line = {
         "metric": "decode_attention_attended_kv_bandwidth_colocated", "unit": "GB/s",
         "value": round(kv_bytes / attn_co_ms / 1e6, 1), "n_gpus": 1, "steps": K, "warmup": Wm,
         "higher_is_better": True, "dtype": args.cache_dtype, "data": "synthetic",
-        "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d, %d layers, partition %d; neighbour: bf16 %d^3 "
+        "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d, %d layers, partition %d, kernel %s; neighbour: bf16 %d^3 "
                                "torch.matmul on a second stream" % (wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, layers,
-                                                                   part, n)},
+                                                                   part, args.kernel, nb.n),
+                   "attention_cus": args.attention_cus or total_cus,
+                   "gemm_cus": total_cus - args.attention_cus if args.attention_cus else total_cus},
         "attention_alone_GBps": round(kv_bytes / attn_alone_ms / 1e6, 1),
         "attention_contended_GBps": round(kv_bytes / attn_co_ms / 1e6, 1),
         "attention_ms_alone": round(attn_alone_ms, 4), "attention_ms_contended": round(attn_co_ms, 4),
-        "gemm_alone_TFLOPs": round(flop / gemm_alone_ms / 1e9, 1),
-        "gemm_contended_TFLOPs": round(flop / gemm_co_ms / 1e9, 1) if inside else None,
-        "gemm_ms_alone": round(gemm_alone_ms, 4), "gemm_ms_contended": round(gemm_co_ms, 4) if inside else None,
-        "gemms_inside_attention_window": len(inside),
+        "gemm_alone_TFLOPs": nb.tflops(gemm_alone_ms),
+        "gemm_contended_TFLOPs": nb.tflops(gemm_co_ms) if gemm_co_ms else None,
+        "gemm_ms_alone": round(gemm_alone_ms, 4), "gemm_ms_contended": round(gemm_co_ms, 4) if gemm_co_ms else None,
+        "gemms_inside_attention_window": n_inside,
     }
     print(json.dumps(line), flush=True)
     return 0
@@ -535,24 +524,107 @@ def graph_replay(args, wl, st, one_step, out, bytes_per_token, layers, part):
     return 0 if same else 1
 
 
+def graph_table(args, wl, st, out, ws, bytes_per_token, layers, part, flags):
+    """Sec. 3.2.2 to its sketch: steps recorded for capacities on an interval grid, the smallest fit
+    replayed for a batch of n rows (surplus rows padded).  For each capacity: GPU time per step and CPU
+    time to enqueue one, eager (one adr_decode_step per layer) against one graph launch."""
+    K, Wm = args.steps, args.warmup
+    b = st["batch"]
+    interval = max(wl.B // 4, 1)
+    seq_buf = st["seq_lens"][0].clone()
+    side = torch.cuda.Stream()
+
+    def make_table(stream, table_flags):
+        return adr.GraphTable(out, st["q"], st["k_new"], st["v_new"], st["caches"], st["table"], seq_buf, wl.scale,
+                              st["max_len"], part, ws, interval, wl.B, stream, flags=table_flags)
+
+    def set_rows(step, n):
+        seq = st["seq_lens"][step].clone()
+        seq[n:] = 0
+        seq_buf.copy_(seq)
+        return int(st["seq_lens"][step][:n].sum().item())
+
+    def timed(fn, stream):
+        torch.cuda.synchronize()
+        cpu = 0.0
+        t0 = time.perf_counter()
+        with torch.cuda.stream(stream):
+            for _ in range(K):
+                c0 = time.perf_counter()
+                fn()
+                cpu += time.perf_counter() - c0
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / K * 1e3, cpu / K * 1e3
+
+    def eager(n):
+        for cache in st["caches"]:
+            adr.adr_decode_step(out[:n], st["q"][:n], st["k_new"][:n], st["v_new"][:n], cache, st["table"][:n],
+                                seq_buf[:n], wl.scale, st["max_len"], part, ws, None, flags)
+
+    table = make_table(side, flags)
+    rows = []
+    # every timed step rewrites the same token slots, so the caches stay as they are
+    for n in sorted({wl.B, wl.B - 1, 3 * wl.B // 4, wl.B // 2 + 1, wl.B // 4, 1}):
+        cap = table.capacity(n)
+        tokens = set_rows(Wm, n)
+        for _ in range(Wm):
+            eager(n)
+            table.launch(n, side)
+        eager_ms, eager_cpu = timed(lambda: eager(n), side)
+        want = out[:n].clone()
+        graph_ms, graph_cpu = timed(lambda: table.launch(n, side), side)
+        same = bool(torch.equal(out[:n], want)) and bool(torch.all(out[n:cap] == 0))
+        rows.append({"rows": n, "capacity": cap, "attended_tokens_per_layer": tokens,
+                     "eager_ms_per_step": round(eager_ms, 4), "graph_ms_per_step": round(graph_ms, 4),
+                     "cpu_enqueue_us_per_layer_eager": round(eager_cpu / layers * 1e3, 2),
+                     "cpu_enqueue_us_per_step_graph": round(graph_cpu * 1e3, 2),
+                     "gpu_us_per_layer_graph": round(graph_ms / layers * 1e3, 2),
+                     "graph_GBps": round(layers * tokens * bytes_per_token / graph_ms / 1e6, 1),
+                     "replayed_output_equals_eager": same})
+        log("graph table: %s" % json.dumps(rows[-1]))
+    table.destroy()
+
+    # a table for a stream confined to three quarters of the compute units: the recording cannot ask the
+    # stream for its mask, so without ADR_GRID_CUS the grid is sized for the whole chip
+    total_cus = torch.cuda.get_device_properties(0).multi_processor_count
+    n_masked = 3 * total_cus // 4
+    handle = adr.adr_stream_create_cu_mask([i < n_masked for i in range(total_cus)])
+    masked = torch.cuda.ExternalStream(handle)
+    set_rows(Wm, wl.B)
+    masked_rows = {}
+    try:
+        eager_ms, _ = timed(lambda: eager(wl.B), masked)        # asks the stream: grid of n_masked workgroups
+        masked_rows["eager_ms_per_step"] = round(eager_ms, 4)
+        for name, f in (("graph_grid_for_whole_chip", flags), ("graph_with_ADR_GRID_CUS", flags | adr.GRID_CUS(n_masked))):
+            t = make_table(masked, f)
+            for _ in range(Wm):
+                t.launch(wl.B, masked)
+            ms, _ = timed(lambda: t.launch(wl.B, masked), masked)
+            masked_rows[name + "_ms_per_step"] = round(ms, 4)
+            torch.cuda.synchronize()
+            t.destroy()
+    finally:
+        torch.cuda.synchronize()
+        adr.adr_stream_destroy(handle)
+    line = {"metric": "decode_step_graph_table", "unit": "ms", "n_gpus": 1, "steps": K, "warmup": Wm,
+            "dtype": args.cache_dtype, "data": "synthetic",
+            "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d, %d layers, partition %d; capacities %s" % (
+                wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, layers, part, list(range(interval, wl.B + 1, interval)))},
+            "rows": rows, "masked_stream": dict(masked_rows, attention_cus=n_masked)}
+    print(json.dumps(line), flush=True)
+    return 0 if all(r["replayed_output_equals_eager"] for r in rows) else 1
+
+
 def cu_sweep(args, wl, st, one_step, bytes_per_token, layers, part):
     """Sec. 3.3's question on this chip: how much attention bandwidth does a fraction of the compute
     units obtain, and what does the neighbour lose?  The attention runs on a stream whose queue is
     masked to the first n compute-unit bits, the matrix products on a stream masked to the rest."""
     K, Wm = args.steps, args.warmup
     b = st["batch"]
-    dev = "cuda:0"
     total_cus = torch.cuda.get_device_properties(0).multi_processor_count
-    n = 8192
-    ga = W.randn_bf16((n, n), wl.seed + 50, dev)
-    gb = W.randn_bf16((n, n), wl.seed + 51, dev)
-    gc = torch.empty((n, n), dtype=torch.bfloat16, device=dev)
-    flop = 2.0 * n ** 3
+    nb = Neighbour(wl)
     tokens = [int(b.lens_before.sum()) + wl.B * (s + 1) for s in range(Wm, Wm + K)]
     kv_bytes = layers * sum(tokens) * bytes_per_token
-
-    def ev():
-        return torch.cuda.Event(enable_timing=True)
 
     def attention_pass():
         for s in range(Wm, Wm + K):
@@ -561,14 +633,14 @@ def cu_sweep(args, wl, st, one_step, bytes_per_token, layers, part):
     for s in range(Wm):
         one_step(s)
     for _ in range(3):
-        torch.matmul(ga, gb, out=gc)
+        nb.product()
     torch.cuda.synchronize()
     rows = []
     for n_attn in range(32, total_cus + 1, 32):
         ha = adr.adr_stream_create_cu_mask([i < n_attn for i in range(total_cus)])
         sa = torch.cuda.ExternalStream(ha)
         row = {"attention_cus": n_attn, "gemm_cus": total_cus - n_attn}
-        a0, a1 = ev(), ev()
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         with torch.cuda.stream(sa):
             attention_pass()                      # warm-up on this stream
             a0.record(); attention_pass(); a1.record()
@@ -578,33 +650,12 @@ def cu_sweep(args, wl, st, one_step, bytes_per_token, layers, part):
         if n_attn < total_cus:
             hb = adr.adr_stream_create_cu_mask([i >= n_attn for i in range(total_cus)])
             sb = torch.cuda.ExternalStream(hb)
-            g0, g1 = ev(), ev()
-            with torch.cuda.stream(sb):
-                torch.matmul(ga, gb, out=gc)
-                g0.record()
-                for _ in range(8):
-                    torch.matmul(ga, gb, out=gc)
-                g1.record()
-            torch.cuda.synchronize()
-            gemm_ms = g0.elapsed_time(g1) / 8
-            row["gemm_alone_TFLOPs"] = round(flop / gemm_ms / 1e9, 1)
-            n_gemm = max(4, int(math.ceil(2.0 * alone_ms / gemm_ms)) + 2)
-            marks = [ev() for _ in range(n_gemm + 1)]
-            c0, c1 = ev(), ev()
-            with torch.cuda.stream(sb):
-                marks[0].record()
-                for i in range(n_gemm):
-                    torch.matmul(ga, gb, out=gc)
-                    marks[i + 1].record()
-            with torch.cuda.stream(sa):
-                c0.record(); attention_pass(); c1.record()
-            torch.cuda.synchronize()
-            co_ms = c0.elapsed_time(c1)
-            inside = [marks[i].elapsed_time(marks[i + 1]) for i in range(n_gemm)
-                      if c0.elapsed_time(marks[i]) >= 0 and marks[i + 1].elapsed_time(c1) >= 0]
+            gemm_ms = nb.alone_ms(sb)
+            row["gemm_alone_TFLOPs"] = nb.tflops(gemm_ms)
+            co_ms, gemm_co_ms, n_inside = side_by_side(attention_pass, sa, nb, sb, alone_ms, gemm_ms)
             row["attention_contended_GBps"] = round(kv_bytes / co_ms / 1e6, 1)
-            row["gemm_contended_TFLOPs"] = round(flop / float(np.mean(inside)) / 1e9, 1) if inside else None
-            row["gemms_inside_attention_window"] = len(inside)
+            row["gemm_contended_TFLOPs"] = nb.tflops(gemm_co_ms) if gemm_co_ms else None
+            row["gemms_inside_attention_window"] = n_inside
             del sb
             adr.adr_stream_destroy(hb)
         del sa
@@ -613,9 +664,9 @@ def cu_sweep(args, wl, st, one_step, bytes_per_token, layers, part):
         rows.append(row)
     line = {"metric": "decode_attention_bandwidth_vs_compute_units", "unit": "GB/s", "n_gpus": 1, "steps": K,
             "warmup": Wm, "dtype": args.cache_dtype, "data": "synthetic",
-            "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d, %d layers, partition %d; neighbour: bf16 %d^3 "
-                                   "torch.matmul on the complementary compute units" % (
-                                       wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, layers, part, n)},
+            "config": {"workload": "%s: B=%d Hq=%d Hkv=%d d=%d, %d layers, partition %d, kernel %s; neighbour: bf16 "
+                                   "%d^3 torch.matmul on the complementary compute units" % (
+                                       wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, layers, part, args.kernel, nb.n)},
             "total_cus": total_cus, "rows": rows}
     print(json.dumps(line), flush=True)
     return 0

@@ -329,6 +329,54 @@ int adr_need_offload(const adr_request_tokens *req, const adr_request_tokens *lo
 int adr_graph_capacity(int n, int interval, int max_capacity);
 
 /*
+ * Table of pre-recorded decode steps (Sec. 3.2.2, "Kernel Pre-launching": the executor's kernels
+ * are launched from recorded graphs, because launching them one by one costs more CPU time than
+ * they take on the GPU; graphs exist for batch capacities on an interval grid and a batch replays
+ * the smallest one that holds it).
+ *
+ * adr_graph_table_create records, for every capacity interval, 2*interval, ..., max_capacity (a
+ * multiple of interval), one step of that many rows -- adr_decode_step for each of the n_layers
+ * caches in turn, on the buffers described by *buffers -- from capture_stream (a stream other than
+ * the default one, idle, which the call leaves idle), and instantiates the graphs.  The buffers must
+ * hold max_capacity rows and outlive the table; `caches` is a HOST array that is only read during
+ * the call.  This call allocates (graphs); launching does not.
+ * adr_graph_table_launch replays, on `stream`, the smallest recorded capacity >= n_rows
+ * (ADR_ERR_SHAPE if there is none).  Before each launch the caller writes the step's inputs into
+ * the buffers; rows from n_rows up to that capacity must be padded rows (seq_lens 0), which append
+ * nothing, read no cache memory and get a zero output row.  Replays of one table must not overlap
+ * each other (they share the buffers and the workspace).
+ * adr_graph_table_capacity: the capacity a batch of n_rows would replay, or -1.
+ * A table for a stream confined to some compute units is recorded with ADR_GRID_CUS(n) in
+ * buffers->flags and launched on that stream: the recording stream cannot be asked for its mask.
+ */
+typedef struct adr_step_buffers {
+    void *out;              /* [max_capacity][Hq][d] */
+    adr_dtype out_dtype;
+    float *lse;             /* optional [max_capacity][Hq] */
+    const void *q;          /* bf16 [max_capacity][Hq][d], rows q_row_stride elements apart */
+    int64_t q_row_stride;
+    const void *k_new, *v_new; /* bf16 [max_capacity][Hkv][d], rows new_row_stride elements apart */
+    int64_t new_row_stride;
+    const adr_kv_cache *caches; /* HOST array: the layers' caches, attended in this order */
+    int n_layers;
+    const int32_t *block_table; /* [max_capacity][max_pages_per_req] */
+    int max_pages_per_req;
+    const int32_t *seq_lens;    /* [max_capacity]: lengths after the append; 0 = padded row */
+    int Hq;
+    float scale;
+    int max_seq_len, partition_tokens;
+    void *workspace;            /* adr_decode_workspace_bytes(max_capacity, ...) bytes */
+    size_t workspace_bytes;
+    unsigned flags;
+} adr_step_buffers;
+typedef struct adr_graph_table adr_graph_table;
+int adr_graph_table_create(adr_graph_table **table, const adr_step_buffers *buffers, int interval,
+                           int max_capacity, void *capture_stream);
+int adr_graph_table_capacity(const adr_graph_table *table, int n_rows);
+int adr_graph_table_launch(adr_graph_table *table, int n_rows, void *stream);
+int adr_graph_table_destroy(adr_graph_table *table);
+
+/*
  * Self-check of the resident-workgroup kernel (ADR_KERNEL_MFMA): its waves hand
  * work to each other through flags in on-chip memory, and every wait on such a
  * flag is bounded.  When one expires the kernel still runs to its end, but no row of

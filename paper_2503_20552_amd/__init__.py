@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     adr_graph_capacity, adr_pack_qkv, adr_scatter_rows, adr_stream_create_cu_mask, adr_stream_destroy, adr_stream_fault_count, adr_decode_read_status, adr_decode_kernel_choice, adr_kernel_name,
     adr_debug_bounds_status, debug_library, adr_status_string,
     adr_version,
-    library_path, load_library,
+    GraphTable, library_path, load_library,
 )

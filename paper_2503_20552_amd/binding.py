@@ -35,6 +35,7 @@ EXPORTS = ("adr_kv_append", "adr_decode_workspace_bytes", "adr_decode_attention"
            "adr_decode_read_status", "adr_decode_kernel_choice", "adr_kernel_name", "adr_debug_bounds_status",
            "adr_offload_bound_mem", "adr_offload_bound_comp", "adr_offload_bound", "adr_need_offload",
            "adr_graph_capacity", "adr_pack_qkv", "adr_scatter_rows",
+           "adr_graph_table_create", "adr_graph_table_capacity", "adr_graph_table_launch", "adr_graph_table_destroy",
            "adr_status_string", "adr_version")
 
 
@@ -53,6 +54,17 @@ class _CCache(ctypes.Structure):
                 ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
                 ("num_pages", ctypes.c_int), ("page_size", ctypes.c_int),
                 ("Hkv", ctypes.c_int), ("d", ctypes.c_int), ("dtype", ctypes.c_int)]
+
+
+class _CStepBuffers(ctypes.Structure):
+    _fields_ = [("out", ctypes.c_void_p), ("out_dtype", ctypes.c_int), ("lse", ctypes.c_void_p),
+                ("q", ctypes.c_void_p), ("q_row_stride", ctypes.c_int64),
+                ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p), ("new_row_stride", ctypes.c_int64),
+                ("caches", ctypes.POINTER(_CCache)), ("n_layers", ctypes.c_int),
+                ("block_table", ctypes.c_void_p), ("max_pages_per_req", ctypes.c_int),
+                ("seq_lens", ctypes.c_void_p), ("Hq", ctypes.c_int), ("scale", ctypes.c_float),
+                ("max_seq_len", ctypes.c_int), ("partition_tokens", ctypes.c_int),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t), ("flags", ctypes.c_uint)]
 
 
 class _CBoundsRecord(ctypes.Structure):
@@ -158,6 +170,14 @@ def _declare(lib):
     lib.adr_kernel_name.argtypes = [i32]
     lib.adr_debug_bounds_status.restype = i32
     lib.adr_debug_bounds_status.argtypes = [ctypes.POINTER(_CBoundsRecord), i32]
+    lib.adr_graph_table_create.restype = i32
+    lib.adr_graph_table_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(_CStepBuffers), i32, i32, vp]
+    lib.adr_graph_table_capacity.restype = i32
+    lib.adr_graph_table_capacity.argtypes = [vp, i32]
+    lib.adr_graph_table_launch.restype = i32
+    lib.adr_graph_table_launch.argtypes = [vp, i32, vp]
+    lib.adr_graph_table_destroy.restype = i32
+    lib.adr_graph_table_destroy.argtypes = [vp]
     return lib
 
 
@@ -507,3 +527,41 @@ def adr_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
     _check(load_library().adr_probe_copy(dst.data_ptr(), src.data_ptr(), n - n % 16,
                                          _stream_handle(stream)), "adr_probe_copy")
 
+
+class GraphTable:
+    """Pre-recorded decode steps for batch capacities interval, 2*interval, ..., max_capacity
+    (adr_graph_table_*).  The tensors are the step's fixed buffers, sized for max_capacity rows; the
+    caller overwrites their contents before each launch and keeps rows >= n padded (seq_lens 0)."""
+
+    def __init__(self, out, q, k_new, v_new, caches, block_table, seq_lens, scale, max_seq_len, partition_tokens,
+                 workspace, interval, max_capacity, capture_stream, lse=None, flags=KERNEL_AUTO):
+        lib = load_library()
+        odt, lse_ptr, qp, qstride, B, Hq, ws_ptr, ws_bytes = _attention_args(out, q, caches[0], block_table, seq_lens,
+                                                                             workspace, lse)
+        if B != max_capacity:
+            raise ValueError("the buffers must hold max_capacity rows")
+        kp, kstride = _rows_view(k_new, "k_new")
+        vp_, vstride = _rows_view(v_new, "v_new")
+        if kstride != vstride:
+            raise ValueError("k_new and v_new must share one row stride")
+        layer_structs = (_CCache * len(caches))(*[c.c_struct() for c in caches])
+        desc = _CStepBuffers(out.data_ptr(), odt, lse_ptr, qp, qstride, kp, vp_, kstride, layer_structs, len(caches),
+                             _i32(block_table, "block_table"), block_table.shape[1], _i32(seq_lens, "seq_lens"), Hq,
+                             float(scale), int(max_seq_len), int(partition_tokens), ws_ptr, ws_bytes, int(flags))
+        self._keep = (out, q, k_new, v_new, caches, block_table, seq_lens, workspace, lse)   # the graphs point into these
+        self._handle = ctypes.c_void_p()
+        self._lib = lib
+        _check(lib.adr_graph_table_create(ctypes.byref(self._handle), ctypes.byref(desc), int(interval),
+                                          int(max_capacity), _stream_handle(capture_stream)), "adr_graph_table_create")
+
+    def capacity(self, n_rows: int) -> int:
+        return int(self._lib.adr_graph_table_capacity(self._handle, int(n_rows)))
+
+    def launch(self, n_rows: int, stream=None) -> None:
+        _check(self._lib.adr_graph_table_launch(self._handle, int(n_rows), _stream_handle(stream)),
+               "adr_graph_table_launch")
+
+    def destroy(self) -> None:
+        if self._handle:
+            _check(self._lib.adr_graph_table_destroy(self._handle), "adr_graph_table_destroy")
+            self._handle = ctypes.c_void_p()

@@ -231,3 +231,22 @@ def test_glue_copies_reject_bad_arguments():
     assert scatter(idx=None) == NULL and scatter(src=None) == NULL
     assert scatter(elems=100) == SHAPE and scatter(ds=128) == SHAPE and scatter(ss=260) == SHAPE
     assert scatter(n=0) == 0
+
+
+def test_graph_table_rejects_bad_arguments_before_recording():
+    lib = adr.load_library()
+    handle = ctypes.c_void_p()
+    caches = (binding._CCache * 1)(cache())
+    desc = binding._CStepBuffers(FAKE, adr.ADR_BF16, None, FAKE, 8 * 128, FAKE, FAKE, 2 * 128, caches, 1, FAKE, 4, FAKE, 8,
+                                 0.1, 64, 0, None, 0, 0)
+    assert lib.adr_graph_table_create(None, ctypes.byref(desc), 4, 8, FAKE) == NULL
+    assert lib.adr_graph_table_create(ctypes.byref(handle), None, 4, 8, FAKE) == NULL
+    assert lib.adr_graph_table_create(ctypes.byref(handle), ctypes.byref(desc), 4, 8, None) == NULL   # needs a stream to record from
+    assert lib.adr_graph_table_create(ctypes.byref(handle), ctypes.byref(desc), 0, 8, FAKE) == SHAPE
+    assert lib.adr_graph_table_create(ctypes.byref(handle), ctypes.byref(desc), 3, 8, FAKE) == SHAPE   # 8 is not a multiple of 3
+    assert lib.adr_graph_table_create(ctypes.byref(handle), ctypes.byref(desc), 8, 4, FAKE) == SHAPE
+    desc.n_layers = 0
+    assert lib.adr_graph_table_create(ctypes.byref(handle), ctypes.byref(desc), 4, 8, FAKE) == SHAPE
+    assert handle.value is None
+    assert lib.adr_graph_table_launch(None, 1, None) == NULL and lib.adr_graph_table_destroy(None) == NULL
+    assert lib.adr_graph_table_capacity(None, 1) == -1
