@@ -558,6 +558,215 @@ __device__ __forceinline__ void read_stage(const char *tile, const uint32_t (&k_
     }
 }
 
+// ---- fp8 cache: operands without widening K, V read transposed -----------------------------
+// K: the bytes of an fp8 K tile feed v_mfma_f32_16x16x32_fp8_fp8 as they are (lane (r, j) holds 8
+// bytes of token r), against the query split into two fp8 numbers per element (below), so that
+// nothing of K is ever widened.
+//
+// V: the B operand of O += P V wants lane (n, j) to hold, for ONE column n, the values of eight
+// tokens -- the transpose of how a V tile lies in memory and in LDS.  gfx950 reads LDS transposed:
+// with ds_read_b64_tr_b8 each lane of a group of sixteen names 8 bytes, and lane i receives byte
+// i % 8 of the pieces named by lanes i / 8 + 2k, k = 0 .. 7.  So when lane h + 2k names "token
+// T(k), columns 16e + 8h .. 16e + 8h + 7", with T = tokens 4j .. 4j + 3 of the pair's first page
+// for k < 4 and of its second page for k >= 4, lane n receives column 16e + n of those eight tokens:
+// the operand for column block e, widened to bf16 without any shuffling in registers.  The
+// accumulator st.o[e] then holds O[head 4j + i][16e + n] in lane (n, j) (a bf16 cache, whose V
+// operand is put together from plain reads by byte permutes, has O[head 4j + i][8n + e] there).
+// Both fp8 tiles are stored with slot c of row t holding chunk c ^ (t & 7), so that the rows these
+// reads touch fall into different LDS banks.
+typedef long i64_t;
+
+struct QueryFp8 {
+    u32x2 hi[4], lo[4]; // q * 2^s = hi + lo, both E4M3 (exact for all but the smallest elements of a row)
+    float unscale;      // 2^-s, this lane's head
+};
+
+__device__ __forceinline__ u32x2 lds_read_tr8(const char *p)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef int i32x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) i32x2 *)p));
+#else
+    return u32x2{0u, 0u};
+#endif
+}
+
+__device__ __forceinline__ f32x4 mfma_fp8(u32x2 a, u32x2 b, f32x4 c)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(__builtin_bit_cast(i64_t, a), __builtin_bit_cast(i64_t, b), c, 0, 0, 0);
+#else
+    return c;
+#endif
+}
+
+// The query rows of an item as fp8 operands: every element is scaled by a power of two chosen per
+// head (the head's largest element lands in [128, 256)) and split into an E4M3 number and the E4M3
+// remainder; bf16 has eight significant bits, the two parts four each, so the split is exact except
+// for elements 2^9 times smaller than the row's largest, which lose low bits worth 2^-17 of that
+// largest element.  The scores are multiplied by 2^-s afterwards.
+__device__ __forceinline__ QueryFp8 query_fp8(const u32x4 (&raw)[4])
+{
+    QueryFp8 q;
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    float amax = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(raw[kk][w])), fabsf(bf16_hi(raw[kk][w]))));
+    amax = max_across_rows(amax); // the head's 128 elements sit in the four lanes (r, 0 .. 3)
+    const uint32_t e = (__float_as_uint(amax) >> 23) & 255u; // biased exponent of the largest element
+    const bool plain = e < 8u || e > 246u;                   // zero, tiny or non-finite rows: no scaling
+    const float scale = plain ? 1.f : __uint_as_float((261u - e) << 23); // 2^(134 - e)
+    q.unscale = plain ? 1.f : __uint_as_float((e - 7u) << 23);          // 2^(e - 134)
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        int hi[2] = {0, 0}, lo[2] = {0, 0};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float x0 = bf16_lo(raw[kk][w]) * scale, x1 = bf16_hi(raw[kk][w]) * scale;
+            const bool upper = (w & 1) != 0;
+            hi[w >> 1] = upper ? __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, hi[w >> 1], true)
+                               : __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, hi[w >> 1], false);
+            const f32x2 back = upper ? __builtin_amdgcn_cvt_pk_f32_fp8(hi[w >> 1], true)
+                                     : __builtin_amdgcn_cvt_pk_f32_fp8(hi[w >> 1], false);
+            lo[w >> 1] = upper ? __builtin_amdgcn_cvt_pk_fp8_f32(x0 - back[0], x1 - back[1], lo[w >> 1], true)
+                               : __builtin_amdgcn_cvt_pk_fp8_f32(x0 - back[0], x1 - back[1], lo[w >> 1], false);
+        }
+        q.hi[kk] = u32x2{(uint32_t)hi[0], (uint32_t)hi[1]};
+        q.lo[kk] = u32x2{(uint32_t)lo[0], (uint32_t)lo[1]};
+    }
+#else
+    (void)raw;
+    q.unscale = 1.f;
+#endif
+    return q;
+}
+
+// K bytes and the two scales of one fp8 ring stage.
+__device__ __forceinline__ void read_stage_fp8(const char *tile, const uint32_t (&k_read)[4], u32x2 (&k8)[4],
+                                               float &k_scale, float &v_scale)
+{
+    typedef Geo<true> geo;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        k8[kk] = *(const u32x2 *)(tile + k_read[kk]);
+    k_scale = *(const float *)(tile + 2 * geo::kTile);
+    v_scale = *(const float *)(tile + 2 * geo::kTile + geo::kScaleSlot);
+}
+
+// The V bytes of a pair of pages (or of one page, when both stages are the same), given the stages'
+// byte offsets in the wave's ring: lanes whose piece belongs to the second page (`second`) name that
+// stage.
+__device__ __forceinline__ void read_v8(const char *ring, int stage_a, int stage_b, bool second,
+                                        const uint32_t (&vt_off)[8], u32x2 (&v8)[8])
+{
+    const char *base = ring + (second ? stage_b : stage_a) + Geo<true>::kTile;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        v8[e] = lds_read_tr8(base + vt_off[e]);
+}
+
+__device__ __forceinline__ void pair_scores_fp8(f32x4 &sa, f32x4 &sb, const u32x2 (&ka)[4], const u32x2 (&kb)[4],
+                                                const QueryFp8 &q)
+{
+    sa = f32x4{0.f, 0.f, 0.f, 0.f};
+    sb = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        sa = mfma_fp8(ka[kk], q.hi[kk], sa);
+        sb = mfma_fp8(kb[kk], q.hi[kk], sb);
+        sa = mfma_fp8(ka[kk], q.lo[kk], sa);
+        sb = mfma_fp8(kb[kk], q.lo[kk], sb);
+    }
+}
+
+// A word of four bytes that clears, in a V operand, the tokens of this lane at or past t1 (tok =
+// index of the lane's first token).
+__device__ __forceinline__ uint32_t tail_mask_fp8(int tok, int t1)
+{
+    return (tok + 0 < t1 ? 0x000000ffu : 0u) | (tok + 1 < t1 ? 0x0000ff00u : 0u) | (tok + 2 < t1 ? 0x00ff0000u : 0u) |
+           (tok + 3 < t1 ? 0xff000000u : 0u);
+}
+
+// O += P V over two pages, column blocks E0 .. E1 - 1; v8: the pair's bytes (four tokens of the
+// first page, then four of the second, per column), widened here.
+template <int E0, int E1>
+__device__ __forceinline__ void pair_pv_fp8(WaveState &st, const PairWeights &w, const u32x2 (&v8)[8])
+{
+#pragma unroll
+    for (int e = E0; e < E1; ++e) {
+        const u32x4 b = fp8x8_to_bf16x8(v8[e]);
+        st.o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w.ah), __builtin_bit_cast(bf16x8, b),
+                                                          st.o[e], 0, 0, 0);
+        st.o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w.al), __builtin_bit_cast(bf16x8, b),
+                                                          st.o[e], 0, 0, 0);
+    }
+}
+
+// One fp8 page on its own: the same steps over 16 tokens, P V as 16x16x16 products.  v8: a transposed
+// read whose first four tokens are the page's.
+__device__ __forceinline__ void single_page_fp8(WaveState &st, const u32x2 (&k8)[4], const u32x2 (&v8)[8],
+                                                const QueryFp8 &q, float score_scale, float p_scale, int tok, int t1,
+                                                int j)
+{
+    f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        s = mfma_fp8(k8[kk], q.hi[kk], s);
+        s = mfma_fp8(k8[kk], q.lo[kk], s);
+    }
+    const bool tail = tok - 4 * j + kPageSize > t1;
+    float sc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        sc[i] = s[i] * score_scale;
+        if (tail && tok + i >= t1)
+            sc[i] = -INFINITY;
+    }
+    float bm = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+    bm = max_across_rows(bm);
+    if (__any(bm > st.m + kMaxSlack)) {
+        const float mn = fmaxf(st.m, bm);
+        const float alpha = fast_exp2(st.m - mn);
+        st.m = mn;
+        st.l *= alpha;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float a = __shfl(alpha, 4 * j + i);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                st.o[e][i] *= a;
+        }
+    }
+    uint32_t ph[4], pl[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float pw = fast_exp2(sc[i] - st.m);
+        st.l += pw;
+        pw *= p_scale;
+        ph[i] = __float_as_uint(pw) & 0xffff0000u;
+        pl[i] = __float_as_uint(pw - __uint_as_float(ph[i]));
+    }
+    u32x2 ah, al;
+    ah[0] = (ph[0] >> 16) | ph[1];
+    ah[1] = (ph[2] >> 16) | ph[3];
+    al[0] = (pl[0] >> 16) | (pl[1] & 0xffff0000u);
+    al[1] = (pl[2] >> 16) | (pl[3] & 0xffff0000u);
+    const uint32_t keep = tail ? tail_mask_fp8(tok, t1) : 0xffffffffu; // rows past the end may hold anything
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const u32x4 wide = fp8x8_to_bf16x8(u32x2{v8[e][0] & keep, 0u});
+        const u32x2 b = u32x2{wide[0], wide[1]};
+        st.o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ah), __builtin_bit_cast(s16x4, b),
+                                                            st.o[e], 0, 0, 0);
+        st.o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, al), __builtin_bit_cast(s16x4, b),
+                                                            st.o[e], 0, 0, 0);
+    }
+}
+
 // STAGES > 0 fixes the ring depth at compile time (the depths of the common shapes: ring
 // positions and wait counts become constants); STAGES = 0 takes it from the parameters.
 // An fp8 pass runs two workgroups per compute unit, i.e. two waves per SIMD: its register
@@ -700,7 +909,8 @@ void decode_stream_kernel(const StreamParams sp)
     // bf16: a row is sixteen 16-byte chunks and a load covers four rows; slot c of row t
     //       holds chunk c ^ t.  Step kk of QK^T reads chunk kk*4 + j of row r (8 elements).
     // fp8:  a row is eight 16-byte chunks and a load covers eight rows; slot c of row t
-    //       holds chunk c ^ (t & 7).  The same 8 elements are the 8-byte piece kk*4 + j.
+    //       holds chunk c ^ (t & 7), in the K tile and in the V tile.  The same 8 elements are the
+    //       8-byte piece kk*4 + j.
     const uint32_t tok_bytes = (uint32_t)Hkv * geo::kRow;
     const uint32_t page_bytes = kPageSize * tok_bytes;
     const int rq = r < G ? r : 0; // query row this lane reads (columns >= G repeat head 0 and are never stored)
@@ -713,7 +923,7 @@ void decode_stream_kernel(const StreamParams sp)
         if (FP8) {
             const int tf = 8 * (i & 1) + (lane >> 3), c = lane & 7; // row / slot of load i (i < 2)
             k_lane[i] = tf * tok_bytes + ((c ^ (tf & 7)) * 16);
-            v_lane[i] = tf * tok_bytes + c * 16;
+            v_lane[i] = k_lane[i];
             const int piece = i * 4 + j;
             k_read[i] = r * D + (((piece >> 1) ^ (r & 7)) * 16) + (piece & 1) * 8;
         } else {
@@ -722,8 +932,19 @@ void decode_stream_kernel(const StreamParams sp)
             k_read[i] = r * (D * 2) + (((i * 4 + j) ^ r) * 16);
         }
     }
-    // V operand: rows 4j + u, the 8 elements 8r .. 8r+7
+    // V operand, bf16: rows 4j + u, the 8 elements 8r .. 8r+7
     const uint32_t v_read = (4 * j) * geo::kRow + r * (geo::kRow / 16);
+    // V operand, fp8, read transposed: lane h + 2k of its group of sixteen names the 8 bytes "token
+    // 4j + (k & 3) of the pair's first (k < 4) or second page, columns 16e + 8h .. +7": half h of
+    // chunk e, which sits in slot e ^ (t & 7) of the token's row.
+    uint32_t vt_off[8];
+    const bool vt_second = (r >> 1) >= 4;
+    {
+        const int vt_row = 4 * j + ((r >> 1) & 3);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            vt_off[e] = vt_row * geo::kRow + ((e ^ (vt_row & 7)) << 4) + 8 * (r & 1);
+    }
     const uint32_t s_lane = lane == 0 ? 0u : 0x7ffffff0u; // scale loads: only lane 0 is in range
     const char *kc = (const char *)p.k_cache;
     const char *vc = (const char *)p.v_cache;
@@ -862,6 +1083,12 @@ void decode_stream_kernel(const StreamParams sp)
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
             qb[kk] = *(const u32x4 *)(myq + (k & 1) * qtile_bytes + q_read[kk]);
+        QueryFp8 q8; // fp8 cache: the same query as two fp8 numbers per element
+        float q_score = p.scale_log2e;
+        if constexpr (FP8) {
+            q8 = query_fp8(qb);
+            q_score *= q8.unscale;
+        }
 
         const int pg_end = ADR_END_PAGE(C);
         for (int pg = ADR_FIRST_PAGE(C); pg < pg_end;) {
@@ -884,42 +1111,92 @@ void decode_stream_kernel(const StreamParams sp)
             const bool pair = pg + kWaves < pg_end && ((real_mask >> second) & 1);
             // the ring is full: S - 1 groups are newer than the head's, S - 2 newer than its successor's
             wait_groups<FP8>(pair ? S - 2 : S - 1);
-            // Copy the stage(s) to registers, hand the slots straight back to the ring and
-            // refill them, so that the loads are under way while this step computes.
-            PageRegs pa;
-            u32x4 ka[4];
-            float ks_a, vs_a;
-            read_stage<FP8>(ring + head * kStageBytes, k_read, v_read, pa, ka, ks_a, vs_a);
-            if (pair) {
-                PageRegs pb;
-                u32x4 kb[4];
-                float ks_b, vs_b;
-                read_stage<FP8>(ring + second * kStageBytes, k_read, v_read, pb, kb, ks_b, vs_b);
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the copies are complete
-                real_mask &= ~((1 << head) | (1 << second));
-                head = second + 1 == S ? 0 : second + 1;
-                occ -= 2;
-                // the two freed slots are refilled in four pieces between the pieces of the arithmetic
-                f32x4 sa, sb;
-                ADR_ISSUE_K();
-                pair_scores(sa, sb, ka, kb, qb);
-                ADR_ISSUE_V();
-                const PairWeights w = pair_softmax(st, pb, sa, sb, p.scale_log2e * ks_a, p.scale_log2e * ks_b,
-                                                   vs_a, vs_b, (pg + kWaves) * kPageSize + 4 * j, C.t1, j);
-                ADR_ISSUE_K();
-                pair_pv<0, 4>(st, w, pa, pb);
-                ADR_ISSUE_V();
-                pair_pv<4, 8>(st, w, pa, pb);
-                pg += 2 * kWaves;
+            if constexpr (FP8) {
+                // Copy the stage(s) to registers (the K bytes as they are, the V bytes transposed), hand the
+                // slots straight back to the ring and refill them, so that the loads are under way while
+                // this step computes.
+                u32x2 ka8[4], v8[8];
+                float ks_a, vs_a;
+                const int stage_a = head * kStageBytes;
+                read_stage_fp8(ring + stage_a, k_read, ka8, ks_a, vs_a);
+                if (pair) {
+                    u32x2 kb8[4];
+                    float ks_b, vs_b;
+                    const int stage_b = second * kStageBytes;
+                    read_stage_fp8(ring + stage_b, k_read, kb8, ks_b, vs_b);
+                    read_v8(ring, stage_a, stage_b, vt_second, vt_off, v8);
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the copies are complete
+                    real_mask &= ~((1 << head) | (1 << second));
+                    head = second + 1 == S ? 0 : second + 1;
+                    occ -= 2;
+                    f32x4 sa, sb;
+                    ADR_ISSUE_K();
+                    pair_scores_fp8(sa, sb, ka8, kb8, q8);
+                    ADR_ISSUE_V();
+                    const int tok_b = (pg + kWaves) * kPageSize + 4 * j;
+                    PageRegs none; // (the V bytes are masked below, not inside the softmax step)
+                    const PairWeights w =
+                        pair_softmax(st, none, sa, sb, q_score * ks_a, q_score * ks_b, vs_a, vs_b, tok_b, C.t1, j);
+                    if (tok_b - 4 * j + kPageSize > C.t1) { // rows of tokens past the end may hold anything
+                        const uint32_t keep = tail_mask_fp8(tok_b, C.t1);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            v8[e][1] &= keep;
+                    }
+                    ADR_ISSUE_K();
+                    pair_pv_fp8<0, 4>(st, w, v8);
+                    ADR_ISSUE_V();
+                    pair_pv_fp8<4, 8>(st, w, v8);
+                    pg += 2 * kWaves;
+                } else {
+                    read_v8(ring, stage_a, stage_a, false, vt_off, v8); // its first four tokens are the page's
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    real_mask &= ~(1 << head);
+                    head = second;
+                    occ -= 1;
+                    while (occ < S)
+                        ADR_ISSUE();
+                    single_page_fp8(st, ka8, v8, q8, q_score * ks_a, vs_a, pg * kPageSize + 4 * j, C.t1, j);
+                    pg += kWaves;
+                }
             } else {
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                real_mask &= ~(1 << head);
-                head = second;
-                occ -= 1;
-                while (occ < S)
-                    ADR_ISSUE();
-                attend_page(st, pa, ka, qb, p.scale_log2e * ks_a, vs_a, pg * kPageSize + 4 * j, C.t1, j);
-                pg += kWaves;
+            // Copy the stage(s) to registers, hand the slots straight back to the ring and
+                // refill them, so that the loads are under way while this step computes.
+                PageRegs pa;
+                u32x4 ka[4];
+                float ks_a, vs_a;
+                read_stage<FP8>(ring + head * kStageBytes, k_read, v_read, pa, ka, ks_a, vs_a);
+                if (pair) {
+                    PageRegs pb;
+                    u32x4 kb[4];
+                    float ks_b, vs_b;
+                    read_stage<FP8>(ring + second * kStageBytes, k_read, v_read, pb, kb, ks_b, vs_b);
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the copies are complete
+                    real_mask &= ~((1 << head) | (1 << second));
+                    head = second + 1 == S ? 0 : second + 1;
+                    occ -= 2;
+                    // the two freed slots are refilled in four pieces between the pieces of the arithmetic
+                    f32x4 sa, sb;
+                    ADR_ISSUE_K();
+                    pair_scores(sa, sb, ka, kb, qb);
+                    ADR_ISSUE_V();
+                    const PairWeights w = pair_softmax(st, pb, sa, sb, p.scale_log2e * ks_a, p.scale_log2e * ks_b,
+                                                       vs_a, vs_b, (pg + kWaves) * kPageSize + 4 * j, C.t1, j);
+                    ADR_ISSUE_K();
+                    pair_pv<0, 4>(st, w, pa, pb);
+                    ADR_ISSUE_V();
+                    pair_pv<4, 8>(st, w, pa, pb);
+                    pg += 2 * kWaves;
+                } else {
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    real_mask &= ~(1 << head);
+                    head = second;
+                    occ -= 1;
+                    while (occ < S)
+                        ADR_ISSUE();
+                    attend_page(st, pa, ka, qb, p.scale_log2e * ks_a, vs_a, pg * kPageSize + 4 * j, C.t1, j);
+                    pg += kWaves;
+                }
             }
         }
 
@@ -1029,21 +1306,39 @@ void decode_stream_kernel(const StreamParams sp)
                             if (bad)
                                 o = f32x4{lse, lse, lse, lse};
                             const int h = Q.kvh * G + g[t];
+                            // fp8: the staged quad at place c4 = 8n + 4q holds columns 16 (4q + u) + n, u = 0 .. 3
+                            // (four stores, each of which the sixteen lanes n fill 64 bytes of); bf16: columns
+                            // c4 .. c4 + 3.
+                            const int col = ((c4[t] & 4) << 4) + (c4[t] >> 3);
                             if (Q.n_parts == 1) {
-                                const int64_t off = ((int64_t)Q.b * p.Hq + h) * D + c4[t];
-                                if (p.out_f32) {
-                                    *(f32x4 *)((float *)p.out + off) = o;
+                                const int64_t row_off = ((int64_t)Q.b * p.Hq + h) * D;
+                                if constexpr (FP8) {
+#pragma unroll
+                                    for (int u = 0; u < 4; ++u) {
+                                        if (p.out_f32)
+                                            ((float *)p.out)[row_off + col + 16 * u] = o[u];
+                                        else
+                                            ((uint16_t *)p.out)[row_off + col + 16 * u] = (uint16_t)f32_to_bf16(o[u]);
+                                    }
+                                } else if (p.out_f32) {
+                                    *(f32x4 *)((float *)p.out + row_off + c4[t]) = o;
                                 } else {
                                     u32x2 packed;
                                     packed[0] = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
                                     packed[1] = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
-                                    *(u32x2 *)((uint16_t *)p.out + off) = packed;
+                                    *(u32x2 *)((uint16_t *)p.out + row_off + c4[t]) = packed;
                                 }
                                 if (p.lse && c4[t] == 0)
                                     p.lse[(int64_t)Q.b * p.Hq + h] = lse;
                             } else {
                                 const int64_t row = ((int64_t)Q.b * p.max_parts + (Q.part << cshift)) * p.Hq + h;
-                                *(f32x4 *)(p.part_o + row * D + c4[t]) = o;
+                                if constexpr (FP8) {
+#pragma unroll
+                                    for (int u = 0; u < 4; ++u)
+                                        p.part_o[row * D + col + 16 * u] = o[u];
+                                } else {
+                                    *(f32x4 *)(p.part_o + row * D + c4[t]) = o;
+                                }
                                 if (c4[t] == 0)
                                     p.part_lse[row] = lse;
                             }
