@@ -139,3 +139,24 @@ def test_debug_build_records_out_of_range_entries_and_computes_what_the_release_
     assert torch.equal(release, debug) and torch.equal(release_lse, debug_lse) and torch.equal(release, again)
     with pytest.raises(adr.AdrError):
         adr.adr_debug_bounds_status()                  # the release build has no such record
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(64, 8), (32, 8)])
+def test_many_one_page_rows_launched_back_to_back(Hq, Hkv):
+    """128 rows of one page each (every item is a single page, three waves of four have nothing to do and the
+    workgroups spend their time handing out and finishing items), sixty launches in a row on one cleared
+    workspace: the regime where the hand-over between items is all there is."""
+    b = small_case(66, Hq, Hkv, 128, np.full(128, 15))
+    c = Resident(b)
+    ref, ref_lse = oracle_attention(b.q, b.k_cache, b.v_cache, b.block_table, b.seq_lens, b.wl.scale)
+    ws = c.workspace(512)
+    outs = torch.full((60,) + c.shape, float("nan"), dtype=torch.float32, device="cuda:0")
+    lses = torch.full((60,) + c.shape[:2], float("nan"), dtype=torch.float32, device="cuda:0")
+    say("one-page rows, 60 launches, Hq=%d" % Hq)
+    for i in range(60):
+        adr.adr_decode_attention(outs[i], c.q, c.cache, c.table, c.seq, b.wl.scale, c.max_len, 512, ws, lses[i],
+                                 adr.KERNEL_MFMA | (adr.WORKSPACE_READY if i else 0))
+    torch.cuda.synchronize()
+    compare(outs[0], lses[0], ref, ref_lse, what="one-page rows")
+    assert torch.equal(outs, outs[0].expand_as(outs)) and torch.equal(lses, lses[0].expand_as(lses))
+    assert adr.adr_decode_read_status(ws, *c.shape, c.max_len, 512) == 0
