@@ -581,14 +581,56 @@ struct QueryFp8 {
     float unscale;      // 2^-s, this lane's head
 };
 
-__device__ __forceinline__ u32x2 lds_read_tr8(const char *p)
+// The transposed reads are written by hand, all eight of a step in one statement, and nothing waits for
+// them there: the compiler would guard each one (it cannot tell the read's target from the ring
+// slots that direct-to-LDS loads are still filling) with a wait for EVERY load in flight, which
+// is exactly what the ring must not do.  The stage read here has landed (wait_groups); the results
+// are valid after the caller's wait for the LDS (settle_copies below), which takes them as operands
+// so that nothing reads them earlier.
+__device__ __forceinline__ void lds_read_tr8_x8(const uint32_t (&addr)[8], u32x2 (&v)[8])
 {
 #if defined(__HIP_DEVICE_COMPILE__)
-    typedef int i32x2 __attribute__((ext_vector_type(2)));
-    return __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) i32x2 *)p));
+    asm volatile("ds_read_b64_tr_b8 %0, %8 offset:%16\n\t"
+                 "ds_read_b64_tr_b8 %1, %9 offset:%16\n\t"
+                 "ds_read_b64_tr_b8 %2, %10 offset:%16\n\t"
+                 "ds_read_b64_tr_b8 %3, %11 offset:%16\n\t"
+                 "ds_read_b64_tr_b8 %4, %12 offset:%16\n\t"
+                 "ds_read_b64_tr_b8 %5, %13 offset:%16\n\t"
+                 "ds_read_b64_tr_b8 %6, %14 offset:%16\n\t"
+                 "ds_read_b64_tr_b8 %7, %15 offset:%16"
+                 : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+                 : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3]), "v"(addr[4]), "v"(addr[5]), "v"(addr[6]),
+                   "v"(addr[7]), "n"(Geo<true>::kTile)
+                 : "memory");
 #else
-    return u32x2{0u, 0u};
+    for (int e = 0; e < 8; ++e)
+        v[e] = u32x2{addr[e], 0u};
 #endif
+}
+
+// Wait for every LDS read of this wave.  What was read (transposed V pieces, K bytes, scales) goes
+// through the statement, so that no use of it is scheduled above the wait, and the compiler, which
+// inserts its own waits for the reads it knows of in front of this statement, has none left to
+// place later on, where a wait for an LDS read would also wait for a page-table entry that is
+// still on its way.
+__device__ __forceinline__ void settle_copies(u32x2 (&v8)[8], u32x2 (&ka)[4], float &s0, float &s1)
+{
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(v8[0]), "+v"(v8[1]), "+v"(v8[2]), "+v"(v8[3]), "+v"(v8[4]), "+v"(v8[5]), "+v"(v8[6]),
+                   "+v"(v8[7]), "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]), "+v"(s0), "+v"(s1)
+                 :
+                 : "memory");
+}
+
+__device__ __forceinline__ void settle_copies(u32x2 (&v8)[8], u32x2 (&ka)[4], u32x2 (&kb)[4], float &s0, float &s1,
+                                              float &s2, float &s3)
+{
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(v8[0]), "+v"(v8[1]), "+v"(v8[2]), "+v"(v8[3]), "+v"(v8[4]), "+v"(v8[5]), "+v"(v8[6]),
+                   "+v"(v8[7]), "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]), "+v"(kb[0]), "+v"(kb[1]),
+                   "+v"(kb[2]), "+v"(kb[3]), "+v"(s0), "+v"(s1), "+v"(s2), "+v"(s3)
+                 :
+                 : "memory");
 }
 
 __device__ __forceinline__ f32x4 mfma_fp8(u32x2 a, u32x2 b, f32x4 c)
@@ -663,10 +705,12 @@ __device__ __forceinline__ void read_stage_fp8(const char *tile, const uint32_t 
 __device__ __forceinline__ void read_v8(const char *ring, int stage_a, int stage_b, bool second,
                                         const uint32_t (&vt_off)[8], u32x2 (&v8)[8])
 {
-    const char *base = ring + (second ? stage_b : stage_a) + Geo<true>::kTile;
+    const uint32_t base = lds_address(ring) + (uint32_t)(second ? stage_b : stage_a);
+    uint32_t addr[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-        v8[e] = lds_read_tr8(base + vt_off[e]);
+        addr[e] = base + vt_off[e];
+    lds_read_tr8_x8(addr, v8);
 }
 
 __device__ __forceinline__ void pair_scores_fp8(f32x4 &sa, f32x4 &sb, const u32x2 (&ka)[4], const u32x2 (&kb)[4],
@@ -977,14 +1021,15 @@ void decode_stream_kernel(const StreamParams sp)
     uint32_t ld_head = (uint32_t)C.kvh * geo::kRow;
     int ld_kvh = C.kvh;
     table_ptr ld_bt = (table_ptr)(p.block_table + (int64_t)C.b * p.max_pages);
-    int ld_ok = 0, ld_id = 0;
+    int ld_ok = 0, ld_entry = 0; // ld_entry: the table's entry for the cursor's page, as loaded
 #ifdef ADR_DEBUG_BOUNDS /* the row the cursor is in, for the record of an out-of-pool page id */
 #define ADR_CURSOR_ROW (int)((ld_bt - (table_ptr)p.block_table) / p.max_pages)
 #else
 #define ADR_CURSOR_ROW 0
 #endif
 #define ADR_SETTLE()                                                                              \
-    do { /* move the cursor to the next existing page and fetch its page id */                    \
+    do { /* move the cursor to the next existing page and fetch its table entry (not looked at    \
+            before the page is issued: the load is given the time until then) */                  \
         if (!ld_in_next && ld_pg >= ld_end) {                                                     \
             ld_in_next = 1;                                                                       \
             ld_pg = ADR_FIRST_PAGE(N);                                                            \
@@ -995,8 +1040,7 @@ void decode_stream_kernel(const StreamParams sp)
         }                                                                                         \
         ld_ok = ld_pg < ld_end;                                                                   \
         if (ld_ok)                                                                                \
-            ld_id = pool_tile_checked(ld_bt[ld_pg >> tsh], ld_pg, p.num_pages, tsh, p.bounds,     \
-                                      ADR_CURSOR_ROW);                                            \
+            ld_entry = ld_bt[ld_pg >> tsh];                                                       \
     } while (0)
     // Ring state: `occ` slots starting at `head` are occupied, in issue order; the
     // next load group goes to `tail`.  real_mask marks the slots that hold a page.
@@ -1012,10 +1056,11 @@ void decode_stream_kernel(const StreamParams sp)
         pend_tile = ring + tail * kStageBytes;                                                    \
         pend_ok = ld_ok;                                                                          \
         if (ld_ok) {                                                                              \
-            pend_id = ld_id;                                                                      \
+            pend_id = pool_tile_checked(ld_entry, ld_pg, p.num_pages, tsh, p.bounds,              \
+                                        ADR_CURSOR_ROW);                                          \
             pend_head = ld_head;                                                                  \
-            pend_scale = (uint32_t)((ld_id >> tsh) * Hkv + ld_kvh) * 4u;                          \
-            issue_half<FP8, 0>(pend_tile, page_rsrc(kc, ld_id, page_bytes), ks_rsrc, k_lane,      \
+            pend_scale = (uint32_t)((pend_id >> tsh) * Hkv + ld_kvh) * 4u;                        \
+            issue_half<FP8, 0>(pend_tile, page_rsrc(kc, pend_id, page_bytes), ks_rsrc, k_lane,    \
                                s_lane, pend_head, pend_scale);                                    \
             real_mask |= 1 << tail;                                                               \
             ld_pg += kWaves;                                                                      \
@@ -1125,7 +1170,7 @@ void decode_stream_kernel(const StreamParams sp)
                     const int stage_b = second * kStageBytes;
                     read_stage_fp8(ring + stage_b, k_read, kb8, ks_b, vs_b);
                     read_v8(ring, stage_a, stage_b, vt_second, vt_off, v8);
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the copies are complete
+                    settle_copies(v8, ka8, kb8, ks_a, vs_a, ks_b, vs_b); // the copies are complete
                     real_mask &= ~((1 << head) | (1 << second));
                     head = second + 1 == S ? 0 : second + 1;
                     occ -= 2;
@@ -1150,7 +1195,7 @@ void decode_stream_kernel(const StreamParams sp)
                     pg += 2 * kWaves;
                 } else {
                     read_v8(ring, stage_a, stage_a, false, vt_off, v8); // its first four tokens are the page's
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    settle_copies(v8, ka8, ks_a, vs_a);
                     real_mask &= ~(1 << head);
                     head = second;
                     occ -= 1;
