@@ -122,7 +122,8 @@ typedef const __attribute__((address_space(4))) int32_t *table_ptr;
 constexpr int kMaxLdsBytes = 160 * 1024; // LDS of one compute unit
 
 // LDS layout: the ring (kWaves * stages * Geo::kStage), the query tiles
-// (kWaves * 2 * q_rows * 256 bytes), this block, then the staging area
+// (kWaves * q_rows * 256 bytes: one per wave, refilled with the next item's rows as soon as an
+// item's rows have been read out), this block, then the staging area
 // float[nb][kWaves][G][D] for the per-wave results of an item.
 struct alignas(16) Shared {
     Rec rec[kQueue];
@@ -135,7 +136,6 @@ struct alignas(16) Shared {
     int total[2];
     int pref_full[kMaxStreamB + 1];
     int pref_rag[kMaxStreamB + 1];
-    int len[kMaxStreamB];
 };
 
 // largest b < B with pref[b] <= u  (pref is an exclusive prefix sum, pref[0] = 0 <= u; B <= 512);
@@ -154,6 +154,14 @@ __device__ __forceinline__ int find_row(const int *pref, int B, int u, int *at_r
     const int hits = __popcll(__ballot(value <= u));
     *at_row = __builtin_amdgcn_readlane(value, hits - 1);
     return block * 8 + hits - 1;
+}
+
+// A row's length as the scan in the kernel's set-up took it (the row index is the same in all lanes:
+// a scalar load).
+__device__ __forceinline__ int row_length(const StreamParams &sp, int b)
+{
+    const int L = sp.d.seq_lens[__builtin_amdgcn_readfirstlane(b)];
+    return max(min(L, sp.d.max_seq_len), 0);
 }
 
 // cshift: tickets enumerate runs of 1 << cshift partitions (see the kernel's set-up); it.part
@@ -176,12 +184,12 @@ __device__ __forceinline__ Item decode_ticket(const Shared &sh, const StreamPara
         int b, at_row, L, t1;
         if (unit < total_full) {
             b = find_row(sh.pref_full, B, unit, &at_row);
-            L = sh.len[b];
+            L = row_length(sp, b);
             it.part = unit - at_row;
             t1 = (it.part + 1) * pt;
         } else {
             b = find_row(sh.pref_rag, B, unit - total_full, &at_row);
-            L = sh.len[b];
+            L = row_length(sp, b);
             it.part = L / pt; // the full items of the row come before its ragged one
             t1 = L;
         }
@@ -826,7 +834,7 @@ void decode_stream_kernel(const StreamParams sp)
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     const int ring_bytes = kWaves * S * kStageBytes;
     const int qtile_bytes = sp.q_rows * (D * 2);
-    Shared &sh = *(Shared *)(lds_raw + ring_bytes + kWaves * 2 * qtile_bytes);
+    Shared &sh = *(Shared *)(lds_raw + ring_bytes + kWaves * qtile_bytes);
     float *staging = (float *)((char *)&sh + sizeof(Shared)); // [nb][kWaves][G][D]
 
     const int tid = threadIdx.x;
@@ -857,8 +865,6 @@ void decode_stream_kernel(const StreamParams sp)
         for (int i = 0; i < 4; ++i) {
             const int row = tid * 4 + i;
             len4[i] = row < B ? max(min(len4[i], p.max_seq_len), 0) : -1;
-            if (row < B)
-                sh.len[row] = len4[i];
         }
         if (tid < kQueue)
             sh.rec[tid].seq = -1;
@@ -993,7 +999,7 @@ void decode_stream_kernel(const StreamParams sp)
     const char *kc = (const char *)p.k_cache;
     const char *vc = (const char *)p.v_cache;
     char *ring = lds_raw + wave * (S * kStageBytes);
-    char *myq = lds_raw + ring_bytes + wave * (2 * qtile_bytes);
+    char *myq = lds_raw + ring_bytes + wave * qtile_bytes;
     const __amdgpu_buffer_rsrc_t null_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)kc, 0, 0, 0x00020000); // every read is out of range: zeros
     const int scale_range = FP8 ? p.num_pages * Hkv * 4 : 0;
@@ -1104,13 +1110,20 @@ void decode_stream_kernel(const StreamParams sp)
         invalid_run = C.valid ? 0 : invalid_run + 1;
         if (invalid_run == kWaves)
             break;
+        // ---- this item's query rows leave the wave's tile for registers (they landed before the
+        // previous item ended); the tile is then free for the next item's rows.
+        u32x4 qb[4]; // B operand of QK^T: head r's query, chunk order matching the K reads
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            qb[kk] = *(const u32x4 *)(myq + q_read[kk]);
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(qb[0]), "+v"(qb[1]), "+v"(qb[2]), "+v"(qb[3])::"memory");
         // ---- look-ahead loads: the query rows of the next item, and (one wave) the
         // ticket of the item three ahead.  The counter's address may reach its scalar
         // registers through a vector-lane read just before the statement; the five
         // wait states such a value needs before a memory instruction may use it are
         // not inserted around hand-written instructions, hence the s_nop.
         const bool drawer = (k & (kWaves - 1)) == wave;
-        issue_query(myq + ((k + 1) & 1) * qtile_bytes, sp, N, q_lane);
+        issue_query(myq, sp, N, q_lane);
         if (drawer && lane == 0)
             asm volatile("s_nop 4\n\tglobal_atomic_add %0, %1, %2, %3 sc0"
                          : "=&v"(next_ticket)
@@ -1124,10 +1137,6 @@ void decode_stream_kernel(const StreamParams sp)
             st.o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
         st.m = kNegBig;
         st.l = 0.f;
-        u32x4 qb[4]; // B operand of QK^T: head r's query, chunk order matching the K reads
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-            qb[kk] = *(const u32x4 *)(myq + (k & 1) * qtile_bytes + q_read[kk]);
         QueryFp8 q8; // fp8 cache: the same query as two fp8 numbers per element
         float q_score = p.scale_log2e;
         if constexpr (FP8) {
@@ -1171,15 +1180,15 @@ void decode_stream_kernel(const StreamParams sp)
                     read_stage_fp8(ring + stage_b, k_read, kb8, ks_b, vs_b);
                     read_v8(ring, stage_a, stage_b, vt_second, vt_off, v8);
                     settle_copies(v8, ka8, kb8, ks_a, vs_a, ks_b, vs_b); // the copies are complete
+                    f32x4 sa, sb;
+                    const int tok_b = (pg + kWaves) * kPageSize + 4 * j;
+                    PageRegs none; // (the V bytes are masked below, not inside the softmax step)
                     real_mask &= ~((1 << head) | (1 << second));
                     head = second + 1 == S ? 0 : second + 1;
                     occ -= 2;
-                    f32x4 sa, sb;
                     ADR_ISSUE_K();
                     pair_scores_fp8(sa, sb, ka8, kb8, q8);
                     ADR_ISSUE_V();
-                    const int tok_b = (pg + kWaves) * kPageSize + 4 * j;
-                    PageRegs none; // (the V bytes are masked below, not inside the softmax step)
                     const PairWeights w =
                         pair_softmax(st, none, sa, sb, q_score * ks_a, q_score * ks_b, vs_a, vs_b, tok_b, C.t1, j);
                     if (tok_b - 4 * j + kPageSize > C.t1) { // rows of tokens past the end may hold anything
@@ -1217,11 +1226,11 @@ void decode_stream_kernel(const StreamParams sp)
                     float ks_b, vs_b;
                     read_stage<FP8>(ring + second * kStageBytes, k_read, v_read, pb, kb, ks_b, vs_b);
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the copies are complete
+                    // the two freed slots are refilled in four pieces between the pieces of the arithmetic
+                    f32x4 sa, sb;
                     real_mask &= ~((1 << head) | (1 << second));
                     head = second + 1 == S ? 0 : second + 1;
                     occ -= 2;
-                    // the two freed slots are refilled in four pieces between the pieces of the arithmetic
-                    f32x4 sa, sb;
                     ADR_ISSUE_K();
                     pair_scores(sa, sb, ka, kb, qb);
                     ADR_ISSUE_V();
@@ -1557,15 +1566,17 @@ hipError_t launch_rows(const DecodeParams &p, int d, bool fp8, int chunk, hipStr
         return e;
     // LDS plan: the query tiles and the staging buffers of the group size are fixed costs, the
     // ring takes the rest.  bf16: one workgroup per compute unit, two staging buffers (one for
-    // the widest groups).  fp8: the pass is bound by what one wave per SIMD can compute, not by
-    // memory, and its stages are half the size, so two workgroups share a compute unit where
-    // they fit (measured: 1.4x); a third ring stage is then worth more than the second staging
-    // buffer (measured on ragged lengths: +3 to +9 %).
+    // the widest groups).  fp8: a wave spends its time in the dependent chain of a step, not
+    // waiting for memory, and its stages are half the size, so two workgroups share a compute
+    // unit where they fit (measured: 1.3x; the depth of the ring hardly matters then: two stages
+    // instead of three cost 3 %).  Groups of up to four heads fit three stages and both staging
+    // buffers; wider ones give up the second staging buffer first (measured on ragged lengths: a
+    // third stage is worth 3 to 9 % more than it).
     const int q_rows = (p.G + 3) / 4 * 4;
     const int stage_bytes = fp8 ? Geo<true>::kStage : Geo<false>::kStage;
     const int max_stages = fp8 ? Geo<true>::kMaxStages : Geo<false>::kMaxStages;
     auto fixed_bytes = [&](int staging_buffers) {
-        return sizeof(Shared) + (size_t)kWaves * 2 * q_rows * (D * 2) +
+        return sizeof(Shared) + (size_t)kWaves * q_rows * (D * 2) +
                (size_t)staging_buffers * kWaves * p.G * D * sizeof(float);
     };
     auto stages_for = [&](int workgroups_per_cu, int staging_buffers) {
