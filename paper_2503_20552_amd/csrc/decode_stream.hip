@@ -160,7 +160,8 @@ __device__ __forceinline__ int find_row(const int *pref, int B, int u, int *at_r
 // a scalar load).
 __device__ __forceinline__ int row_length(const StreamParams &sp, int b)
 {
-    const int L = sp.d.seq_lens[__builtin_amdgcn_readfirstlane(b)];
+    // (read through the constant address space: a scalar load, which no load of the ring waits behind)
+    const int L = ((const __attribute__((address_space(4))) int32_t *)sp.d.seq_lens)[__builtin_amdgcn_readfirstlane(b)];
     return max(min(L, sp.d.max_seq_len), 0);
 }
 
