@@ -108,9 +108,10 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
 
     // Two page buffers used alternately (K tile in LDS + V rows in registers),
     // so that the loads of page n+1 are in flight while page n is consumed.  A
-    // wave always issues the next load group, even past its last page (it then
-    // re-reads its last page, a cache hit), which keeps the number of loads in
-    // flight fixed: "all but the newest eight" is always the page to consume.
+    // wave always issues the next load group, even past its last page (then with a
+    // descriptor of zero bytes: the loads return zeros and fetch nothing), which
+    // keeps the number of loads in flight fixed: "all but the newest eight" is
+    // always the page to consume.
     // Page ids are fetched two pages ahead.
     int pg = t0 / kPageSize + wave;
     if (pg < pg_end) {
@@ -126,7 +127,8 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
         for (;;) {
             page = page_next;
             page_next = ADR_TILE(min(pg + 2 * kWaves, last));
-            load_page(B, tile1, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes),
+            const uint32_t range_b = pg + kWaves <= last ? page_bytes : 0u;
+            load_page(B, tile1, page_rsrc(kc, page, page_bytes, range_b), page_rsrc(vc, page, page_bytes, range_b),
                       k_lane, v_lane, tok_bytes);
             wait_older_page();
             read_k_operand(ka, tile0, k_read);
@@ -136,7 +138,8 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
                 break;
             page = page_next;
             page_next = ADR_TILE(min(pg + 2 * kWaves, last));
-            load_page(A, tile0, page_rsrc(kc, page, page_bytes), page_rsrc(vc, page, page_bytes),
+            const uint32_t range_a = pg + kWaves <= last ? page_bytes : 0u;
+            load_page(A, tile0, page_rsrc(kc, page, page_bytes, range_a), page_rsrc(vc, page, page_bytes, range_a),
                       k_lane, v_lane, tok_bytes);
             wait_older_page();
             read_k_operand(ka, tile1, k_read);

@@ -33,6 +33,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t page_rsrc(const char *cache, i
                                              (int)page_bytes, 0x00020000);
 }
 
+// The same with a range of its own: zero bytes make every lane's read out of range (zeros come
+// back, and nothing is fetched).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t page_rsrc(const char *cache, int page,
+                                                            uint32_t page_bytes, uint32_t range_bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)(cache + (size_t)page * page_bytes), 0,
+                                             (int)range_bytes, 0x00020000);
+}
+
 // Issue the eight 16-byte loads of one page (this lane's share of K and V for
 // one kv-head): four K loads that land in the LDS tile `ktile` (lane l of load
 // i fills bytes [i*1024 + 16 l, +16) of the tile), four V loads into registers.
