@@ -365,6 +365,15 @@ __device__ __forceinline__ Item fetch(Rec &rec, int seq, const Waits &w, const i
     it.part = __builtin_amdgcn_readfirstlane(hi[0]);
     it.t1 = __builtin_amdgcn_readfirstlane(hi[1]);
     it.n_parts = __builtin_amdgcn_readfirstlane(hi[2]);
+    if (!ok) {
+        // The record never came, and the slot holds whatever the LDS held: the wave goes on as if the
+        // item were past the end, with the fields of such an item.  (The load cursor starts from the
+        // item's partition whether the item is valid or not; a negative page index out of a stale
+        // word would pass for a page in front of the item's end and send a scalar load, which no
+        // descriptor bounds, to a wild address.)
+        it.b = it.kvh = it.part = it.t1 = 0;
+        it.n_parts = 1;
+    }
     return it;
 }
 
@@ -1045,7 +1054,7 @@ void decode_stream_kernel(const StreamParams sp)
             ld_kvh = N.kvh;                                                                       \
             ld_bt = (table_ptr)(p.block_table + (int64_t)N.b * p.max_pages);                      \
         }                                                                                         \
-        ld_ok = ld_pg < ld_end;                                                                   \
+        ld_ok = (unsigned)ld_pg < (unsigned)ld_end;                                               \
         if (ld_ok)                                                                                \
             ld_entry = ld_bt[ld_pg >> tsh];                                                       \
     } while (0)

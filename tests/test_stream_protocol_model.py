@@ -21,7 +21,8 @@ import pytest
 
 KW = 4; KQ = 8
 
-def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshift=0, waits_expire=False):
+def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshift=0, waits_expire=False,
+        clear_expired_items=True):
     rnd = random.Random(seed)
     B = len(seq_lens)
     pt_given = pt_arg if pt_arg > 0 else (1 << 30)
@@ -67,6 +68,11 @@ def run(seq_lens, block_table, Hkv, pt_arg, max_seq_len, n_wg, S, NB, seed, cshi
                 if waits_expire:     # the record never came: the wave goes on as if the item were past the end
                     stats["expired"] += 1
                     yield
+                    if not clear_expired_items:
+                        # what the slot holds then is whatever the LDS held: any bit pattern.  The kernel must
+                        # not let it through (clear_expired_items=False plants that mistake)
+                        return dict(valid=False, b=rnd.randrange(-2**31, 2**31), kvh=rnd.randrange(-2**31, 2**31),
+                                    part=rnd.randrange(-2**31, 2**31), t1=rnd.randrange(-2**31, 2**31), n_parts=1)
                     return dict(valid=False, b=0, kvh=0, part=0, t1=0, n_parts=1)
                 yield
             return dict(sh["rec"][idx % KQ]["it"])
@@ -254,3 +260,21 @@ def test_with_every_wait_expiring_the_waves_still_terminate_inside_their_rows(tr
     table = rng.integers(0, 10000, size=(len(lens), maxp)).astype(np.int32)
     stats = run(lens, table, Hkv, pt, int(lens.max()), n_wg, S, NB, trial, cshift, waits_expire=True)
     assert stats["expired"] > 0
+
+
+def test_an_expired_record_fetch_must_hand_on_a_cleared_item():
+    """What a record slot holds when its record never came is arbitrary.  The load cursor starts from the item's
+    partition whether the item is valid or not, so stale fields (a negative partition, say) would send it to pages
+    outside the row's table: the kernel clears the fields of such an item.  Planting the omission here must trip
+    the model's bounds checks for at least one of the schedules."""
+    tripped = 0
+    for trial, lens, Hkv, pt, S, NB, n_wg, cshift in CASES[:40]:
+        rng = np.random.default_rng(300 + trial)
+        maxp = max(1, (int(lens.max()) + 15) // 16)
+        table = rng.integers(0, 10000, size=(len(lens), maxp)).astype(np.int32)
+        try:
+            run(lens, table, Hkv, pt, int(lens.max()), n_wg, S, NB, trial, cshift, waits_expire=True,
+                clear_expired_items=False)
+        except (AssertionError, IndexError, RuntimeError):
+            tripped += 1
+    assert tripped > 0, "stale fields of an expired fetch went unnoticed"
