@@ -262,9 +262,13 @@ int choose_kernel(const adr_kv_cache *cache, int B, int Hq, int max_seq_len, int
     // Measured on MI355X: the resident-workgroup kernel wins on split passes with many items
     // (groups of up to four heads always; wider groups from 2048 (request, kv-head) pairs
     // on: +11 % at 256 requests x 8 kv-heads, G = 8; about even at a quarter of that);
-    // whole-row items and small passes of wide groups run faster one workgroup per item.
+    // whole-row items and small passes of wide groups run faster one workgroup per item, unless
+    // the bound on the lengths allows more than 32 partitions per row: that kernel's grid is sized
+    // from the bound, and on the 70B-shaped workload under a bound of 32 K tokens its workgroups
+    // without a partition make it 90 us against the resident kernel's 84 us (73 us under the
+    // lengths' own maximum).
     const bool splits = partition_tokens > 0 && max_seq_len > partition_tokens;
-    const bool many = (int64_t)B * cache->Hkv >= 2048;
+    const bool many = (int64_t)B * cache->Hkv >= 2048 || max_parts_for(max_seq_len, partition_tokens) > 32;
     // An fp8 cache has the resident-workgroup kernel and the vector-ALU one only.
     if ((fp8 || (splits && (G <= 4 || many))) && adr::decode_stream_supports(d, G, B))
         return KERNEL_STREAM;
@@ -317,7 +321,7 @@ int decode_attention(void *out, adr_dtype out_dtype, float *lse, const void *q, 
     if (kernel < 0)
         return -kernel;
     const int64_t max_parts = max_parts_for(max_seq_len, partition_tokens);
-    if ((int64_t)B * cache->Hkv * max_parts > 0x7fffffffLL)
+    if ((int64_t)B * cache->Hkv * (max_parts + 1) > 0x7fffffffLL) // (+1: the grids take an odd number per row)
         return ADR_ERR_SHAPE;
     const bool split = partition_tokens > 0 && max_parts > 1;
     const WorkspacePlan plan = plan_workspace(B, Hq, d, max_seq_len, partition_tokens);

@@ -33,6 +33,8 @@
 //       Result layout: lane (r, j) holds O[head 4j+i][8r + e].
 #include "mfma_page.h"
 
+#include <algorithm>
+
 namespace adr {
 
 __device__ __forceinline__ void read_k_operand(u32x4 (&ka)[4], const char *ktile,
@@ -43,19 +45,36 @@ __device__ __forceinline__ void read_k_operand(u32x4 (&ka)[4], const char *ktile
         ka[kk] = *(const u32x4 *)(ktile + k_read[kk]);
 }
 
+// Workgroups are numbered row by row: kv-head fastest (the heads of a page are read together),
+// then the row's partitions, `stride` of them; a workgroup takes every stride-th partition of its
+// row from its own on and leaves at once when the row has none for it.  The grid is sized from
+// the caller's bound on the lengths, not from the lengths, so most workgroups may find nothing.
+// Two things were measured on the 70B-shaped workload (1 712 items of 13 312 workgroups, 73 us):
+// (1) the hardware hands consecutive workgroups to its compute units in turn, so when the number of
+// workgroups per row divides the units evenly, a row's few real workgroups fall on the same units
+// row after row: 123 us with 16 partitions per row in the grid, 152 us with 64.  The stride is
+// therefore odd.  (2) Workgroups that find nothing still cost about a nanosecond each, and a loose
+// bound makes tens of thousands of them: the stride stops at kGridStrideMax, and rows with more
+// partitions (rare where this kernel is chosen) have their workgroups loop.
+constexpr int kGridStrideMax = 33;
+__host__ __device__ inline int grid_stride(int max_parts)
+{
+    const int n = max_parts < kGridStrideMax ? max_parts : kGridStrideMax;
+    return n > 1 ? (n | 1) : n;
+}
+
 __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParams p)
 {
     const int Hkv = p.Hkv, G = p.G;
+    const int stride = grid_stride(p.max_parts);
     const int kvh = blockIdx.x % Hkv;
-    const int part = (blockIdx.x / Hkv) % p.max_parts;
-    const int b = blockIdx.x / (Hkv * p.max_parts);
+    const int first_part = (blockIdx.x / Hkv) % stride;
+    const int b = blockIdx.x / (Hkv * stride);
 
     const int L = max(min(p.seq_lens[b], p.max_seq_len), 0);
     const int n_parts = parts_of(L, p.partition_tokens);
-    if (part >= n_parts)
+    if (first_part >= n_parts)
         return;
-    const int t0 = p.partition_tokens > 0 ? part * p.partition_tokens : 0;
-    const int t1 = p.partition_tokens > 0 ? min(L, t0 + p.partition_tokens) : L;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -71,13 +90,6 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
             qb[kk] = *(const u32x4 *)(p.q + (int64_t)b * p.q_row_stride +
                                       (int64_t)(kvh * G + r) * D + (kk * 4 + j) * 8);
     }
-
-    WaveState st;
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-        st.o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-    st.m = kNegBig;
-    st.l = 0.f;
 
     // Byte offsets of this lane.
     //  K load i (to LDS): row t = 4i + j, slot r of that row, which holds chunk r ^ t.
@@ -100,11 +112,21 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
     // scalar loads and stay out of the vector-memory counter the waits rely on.
     typedef const __attribute__((address_space(4))) int32_t *table_ptr;
     table_ptr bt = (table_ptr)(p.block_table + (int64_t)b * p.max_pages);
-    const int pg_end = (t1 + kPageSize - 1) / kPageSize;
 
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     char *tile0 = lds_raw + wave * (kStages * kTileBytes);
     char *tile1 = tile0 + kTileBytes;
+
+    for (int part = first_part; part < n_parts; part += stride) {
+    const int t0 = p.partition_tokens > 0 ? part * p.partition_tokens : 0;
+    const int t1 = p.partition_tokens > 0 ? min(L, t0 + p.partition_tokens) : L;
+    const int pg_end = (t1 + kPageSize - 1) / kPageSize;
+    WaveState st;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        st.o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    st.m = kNegBig;
+    st.l = 0.f;
 
     // Two page buffers used alternately (K tile in LDS + V rows in registers),
     // so that the loads of page n+1 are in flight while page n is consumed.  A
@@ -176,13 +198,15 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeParam
     }
     __syncthreads();
     combine_waves_and_store<D>(p, sm, sl, so, G, b, kvh, part, n_parts);
+    __syncthreads(); // the next partition's K tiles go where the per-wave results lie
+    }
 }
 
 hipError_t launch_decode_mfma(const DecodeParams &p, int d, hipStream_t stream)
 {
     if (d != D)
         return hipErrorInvalidValue;
-    const dim3 grid((unsigned)((int64_t)p.B * p.Hkv * p.max_parts));
+    const dim3 grid((unsigned)((int64_t)p.B * p.Hkv * grid_stride(p.max_parts)));
     size_t lds = (size_t)kWaves * p.G * (D + 2) * sizeof(float); // per-wave results
     if (lds < (size_t)kWaves * kStages * kTileBytes)
         lds = (size_t)kWaves * kStages * kTileBytes;             // K tiles

@@ -60,9 +60,12 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(const DecodeParam
     constexpr int U = kPageSize / TPL;  // load instructions per page
 
     const int Hkv = p.Hkv;
+    // (an odd number of workgroups per row and kv-head: consecutive workgroups go to the compute
+    // units in turn, and with an even number a row's few real ones fall on the same units row after row)
+    const int stride = p.max_parts > 1 ? (p.max_parts | 1) : 1;
     const int kvh = blockIdx.x % Hkv;
-    const int part = (blockIdx.x / Hkv) % p.max_parts;
-    const int b = blockIdx.x / (Hkv * p.max_parts);
+    const int part = (blockIdx.x / Hkv) % stride;
+    const int b = blockIdx.x / (Hkv * stride);
 
     const int L = min(p.seq_lens[b], p.max_seq_len);
     const int n_parts = parts_of(L, p.partition_tokens);
@@ -227,7 +230,7 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(const DecodeParam
 hipError_t launch_decode_valu(const DecodeParams &p, int d, bool fp8, hipStream_t stream)
 {
     const int G = p.G;
-    const dim3 grid((unsigned)((int64_t)p.B * p.Hkv * p.max_parts));
+    const dim3 grid((unsigned)((int64_t)p.B * p.Hkv * (p.max_parts > 1 ? (p.max_parts | 1) : 1)));
     ADR_VALU_CASE(128, 1)
     ADR_VALU_CASE(128, 2)
     ADR_VALU_CASE(128, 4)
