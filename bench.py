@@ -45,12 +45,12 @@ HBM_PEAK_GBS = 8000.0
 # line reports traffic null rather than a stale number.
 MEASURED_TRAFFIC_BYTES = {
     # (workload, kernel[, "fp8"]): (bytes per launch, hash of csrc/ at the time, summary under profiles/)
-    (3, 'decode_stream_kernel'): (2344262481, '54a8e3547e6f99c8', 'profiles/decode_stream_kernel_workload3.md'),
-    (5, 'decode_stream_kernel'): (10533315244, '54a8e3547e6f99c8', 'profiles/decode_stream_kernel_workloads2_5_bf16.md'),
-    (2, 'decode_stream_kernel'): (1447085915, '54a8e3547e6f99c8', 'profiles/decode_stream_kernel_workloads2_5_bf16.md'),
-    (5, 'decode_stream_kernel', 'fp8'): (5457502646, '54a8e3547e6f99c8', 'profiles/decode_stream_kernel_workload5_fp8.md'),
-    (3, 'decode_stream_kernel', 'fp8'): (1214562715, '54a8e3547e6f99c8', 'profiles/decode_stream_kernel_workload5_fp8.md'),
-    (4, 'decode_mfma_kernel'): (347836344, '54a8e3547e6f99c8', 'profiles/decode_mfma_kernel_workload4.md'),
+    (3, 'decode_stream_kernel'): (2344273634, '6766cd555ffaca53', 'profiles/decode_stream_kernel_workload3.md'),
+    (5, 'decode_stream_kernel'): (10533352777, '6766cd555ffaca53', 'profiles/decode_stream_kernel_workloads2_5_bf16.md'),
+    (2, 'decode_stream_kernel'): (1447104494, '6766cd555ffaca53', 'profiles/decode_stream_kernel_workloads2_5_bf16.md'),
+    (5, 'decode_stream_kernel', 'fp8'): (5456117949, '6766cd555ffaca53', 'profiles/decode_stream_kernel_workload5_fp8.md'),
+    (3, 'decode_stream_kernel', 'fp8'): (1214961475, '6766cd555ffaca53', 'profiles/decode_stream_kernel_workload5_fp8.md'),
+    (4, 'decode_mfma_kernel'): (347841203, '6766cd555ffaca53', 'profiles/decode_mfma_kernel_workload4.md'),
 }
 
 
