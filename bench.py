@@ -69,7 +69,7 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def build_state(wl: W.Workload, layers: int, total_steps: int, fp8: bool = False):
+def build_state(wl: W.Workload, layers: int, total_steps: int, fp8: bool = False, length_bound: int = 0):
     dev = "cuda:0"
     b = W.make_batch(wl, device=dev, headroom_tokens=total_steps + 1)
 
@@ -97,6 +97,13 @@ def build_state(wl: W.Workload, layers: int, total_steps: int, fp8: bool = False
     seq_lens = (positions + 1).contiguous()
     table = torch.as_tensor(b.block_table).to(dev)
     max_len = int(b.lens_before.max()) + total_steps
+    if length_bound > max_len:
+        # the bound a serving system knows (its context limit), not the batch's own maximum: the table is
+        # padded to it, nothing else changes
+        pages = -(-length_bound // wl.page_size)
+        wide = torch.zeros((wl.B, pages), dtype=table.dtype, device=dev)
+        wide[:, :table.shape[1]] = table
+        table, max_len = wide, length_bound
     return dict(batch=b, caches=caches, q=q, k_new=k_new, v_new=v_new, positions=positions,
                 seq_lens=seq_lens, table=table, max_len=max_len)
 
@@ -136,6 +143,9 @@ def main():
     ap.add_argument("--cu-sweep", action="store_true",
                     help="with --corun-gemm: repeat the measurement with the attention confined to 32, 64, ... "
                          "compute units and the matrix products to the others")
+    ap.add_argument("--length-bound", type=int, default=0,
+                    help="pass this bound on the lengths (max_seq_len) instead of the batch's own maximum, when it "
+                         "is larger: what a serving system with a fixed context limit would pass")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch adr_probe_copy once on 1 GiB (calibrates profiler byte counters)")
     args = ap.parse_args()
@@ -160,7 +170,7 @@ def main():
 
     t0 = time.time()
     fp8 = args.cache_dtype == "fp8"
-    st = build_state(wl, layers, total_steps, fp8)
+    st = build_state(wl, layers, total_steps, fp8, args.length_bound)
     b = st["batch"]
     elem = 1 if fp8 else 2
     torch.cuda.synchronize()
@@ -241,7 +251,7 @@ def main():
     kernel_name = adr.adr_kernel_name(adr.adr_decode_kernel_choice(st["caches"][0], wl.B, wl.Hq, st["max_len"],
                                                                    part, flags))
     traffic, traffic_source = None, None
-    default_shape = layers == wl.layers and part == wl.partition_tokens
+    default_shape = layers == wl.layers and part == wl.partition_tokens and not args.length_bound
     entry = MEASURED_TRAFFIC_BYTES.get((wl.ident, kernel_name, "fp8") if fp8 else (wl.ident, kernel_name))
     if entry and default_shape and entry[1] == csrc_hash():
         traffic, traffic_source = entry[0], entry[2]
@@ -273,7 +283,7 @@ def main():
                                "merge, lengths %s" % (wl.name, wl.B, wl.Hq, wl.Hkv, wl.d, wl.page_size,
                                                       "fp8-e4m3" if fp8 else "bf16", layers, part, wl.lengths),
                    "kernel": args.kernel, "layers": layers, "partition_tokens": part,
-                   "cache_dtype": args.cache_dtype},
+                   "cache_dtype": args.cache_dtype, "max_seq_len": st["max_len"]},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
         "attended_tokens_per_s": round(attended_tokens / elapsed, 1),
         "roofline": roofline,

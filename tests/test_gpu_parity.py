@@ -535,3 +535,27 @@ def test_graph_recorded_at_a_capacity_serves_smaller_batches_with_padded_rows():
 def test_resident_kernel_reports_no_expired_waits():
     """Runs after the cases above: none of the waves' bounded waits may have expired."""
     assert adr.adr_stream_fault_count() == 0
+
+
+@pytest.mark.parametrize("bound", [None, 8192])
+@pytest.mark.parametrize("kernel", ["grid", "valu", "mfma"])
+def test_rows_of_many_partitions_and_a_loose_bound_on_the_lengths(kernel, bound):
+    """The grids of the one-workgroup-per-item kernels are sized from the caller's bound on the lengths and
+    give a row at most 33 workgroups per kv-head, which loop over the partitions of longer rows: rows of 1, 33,
+    34, 67 and 70 partitions of 64 tokens, under the lengths' own maximum and under a bound twice as large
+    (with the table padded to it)."""
+    lens = [4479, 70, 2200, 1, 64 * 33, 64 * 33 + 1, 64 * 66 + 5, 0]
+    b = small_case(123, 8, 2, 128, [max(L - 1, 0) for L in lens])
+    seq = b.seq_lens.copy()
+    seq[-1] = 0
+    table = b.block_table
+    if bound is not None:
+        wide = np.zeros((table.shape[0], bound // 16), dtype=np.int32)
+        wide[:, :table.shape[1]] = table
+        table = wide
+    say("many partitions, kernel=%s bound=%s" % (kernel, bound))
+    out, lse = gpu_attention(dev(b.q), dev(b.k_cache), dev(b.v_cache), dev(table), dev(seq), b.wl.scale,
+                             partition_tokens=64, flags=KERNELS[kernel], max_seq_len=bound)
+    ref, ref_lse = oracle_attention(b.q, b.k_cache, b.v_cache, b.block_table, seq, b.wl.scale)
+    max_abs, _ = compare(out, lse, ref, ref_lse, what="many partitions %s" % kernel)
+    assert max_abs <= ATOL
