@@ -64,8 +64,10 @@ enum {
     ADR_KERNEL_MFMA = 2, /* matrix-core QK^T and PV (d = 128): resident workgroups pulling
                             (request, partition, kv-head) items; batches of more than 512 rows
                             go out as one launch per 512 rows */
-    ADR_KERNEL_MFMA_GRID = 3, /* matrix cores, one workgroup per (request, partition, kv-head);
-                                 bf16 cache only */
+    ADR_KERNEL_MFMA_GRID = 3, /* matrix cores, one workgroup per (request, partition, kv-head), for up
+                                 to 33 partitions of a request (workgroups loop over the partitions
+                                 of longer ones); its grid is sized from max_seq_len, so a bound far
+                                 above the lengths costs it time; bf16 cache only */
     /* Bit 4: run the partition pass only and leave the merge to a later
      * adr_decode_merge call on the same workspace (rows with one partition are
      * still written to `out` directly).  Lets a caller place the two passes on
